@@ -1,0 +1,151 @@
+"""Seeded synthetic inputs for the ISO layer-shard prefill.
+
+This module only draws random tensors and names workload shapes.  It holds none
+of the method's arithmetic and is the only code shared by the CPU oracle's
+callers and the HIP path's callers: both receive exactly the same tensors.
+
+Workloads follow the model classes the paper evaluates (Section 4.1: dense ~30B
+MHA and ~70B GQA models, batch size 1, prompts of 1k-128k tokens) cut into one
+tensor-parallel shard (Section 2.1, tensor parallelism): the shard keeps
+`n_q_heads`/`n_kv_heads` local heads and `ffn` local MLP columns, and the full
+hidden width.  The paper's weights and prompts are proprietary, so values are
+synthetic: hidden states N(0,1), matrices N(0, 1/fan_in) with fan_in the
+contraction length as stored in the shard, RMSNorm gains 1 + 0.1*N(0,1).
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Dict
+
+import torch
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ffn: int
+    seq: int
+    split: int
+    dtype: str          # "f32" or "bf16"
+    n_layers: int = 1
+    rms_eps: float = 1e-6
+    rope_base: float = 10000.0
+
+    @property
+    def n_qkv(self) -> int:
+        return (self.n_q_heads + 2 * self.n_kv_heads) * self.head_dim
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+    def gemm_flops(self, tokens: int | None = None) -> float:
+        """2*M*N*K over the four projections of one layer."""
+        t = self.seq if tokens is None else tokens
+        h, d, f = self.hidden, self.head_dim, self.ffn
+        per_tok = 2 * h * self.n_qkv + 2 * self.n_q_heads * d * h + 4 * h * f + 2 * f * h
+        return float(per_tok) * t
+
+    def attn_flops(self, q_offset: int = 0, tc: int | None = None) -> float:
+        """4*d*nq per visible (query, key) pair of a causal chunk."""
+        tc = self.seq if tc is None else tc
+        pairs = tc * q_offset + tc * (tc + 1) // 2
+        return 4.0 * self.head_dim * self.n_q_heads * pairs
+
+    def layer_flops(self) -> float:
+        return self.gemm_flops() + self.attn_flops()
+
+
+def split_point(seq: int, frac: float) -> int:
+    """Split used for a fractional split request: nearest multiple of 32."""
+    return int(round(frac * seq / 32.0)) * 32
+
+
+WORKLOADS: Dict[str, Workload] = {
+    w.name: w
+    for w in [
+        # small case the oracle finishes in well under a second
+        Workload("tiny_f32", 256, 4, 4, 64, 688, 128, 64, "f32"),
+        # ~30B MHA model, one TP=4 shard, 2k prompt
+        Workload("30b_tp4_2k", 6656, 13, 13, 128, 4480, 2048, 1024, "bf16"),
+        # ~70B GQA model, one TP=8 shard, 4k prompt
+        Workload("70b_tp8_4k", 8192, 8, 1, 128, 3584, 4096, 2048, "bf16"),
+        # ~70B GQA model, one TP=4 shard, 8k prompt (split swept in tests/bench)
+        Workload("70b_tp4_8k", 8192, 16, 2, 128, 7168, 8192, 4096, "bf16"),
+        # ~70B GQA model, one TP=8 shard, full 80-layer stack, 16k prompt
+        Workload("70b_tp8_16k_stack", 8192, 8, 1, 128, 3584, 16384, 8192, "bf16", n_layers=80),
+    ]
+}
+
+
+def _randn(gen: torch.Generator, *shape: int) -> torch.Tensor:
+    return torch.randn(*shape, generator=gen, dtype=torch.float32)
+
+
+def make_layer(hidden: int, n_q_heads: int, n_kv_heads: int, head_dim: int, ffn: int,
+               seed: int, dtype: torch.dtype) -> Dict[str, torch.Tensor]:
+    """Random weights of one layer shard (CPU tensors, already cast to `dtype`).
+
+    Draw order: w_qkv, w_o, w_gate_up, w_down, g_attn, g_mlp (fp32 draws, then a
+    round-to-nearest-even cast for bf16).
+    """
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    n_qkv = (n_q_heads + 2 * n_kv_heads) * head_dim
+    nqd = n_q_heads * head_dim
+    w = {
+        "w_qkv": _randn(gen, n_qkv, hidden) * hidden ** -0.5,
+        "w_o": _randn(gen, hidden, nqd) * nqd ** -0.5,
+        "w_gate_up": _randn(gen, 2 * ffn, hidden) * hidden ** -0.5,
+        "w_down": _randn(gen, hidden, ffn) * ffn ** -0.5,
+        "g_attn": 1.0 + 0.1 * _randn(gen, hidden),
+        "g_mlp": 1.0 + 0.1 * _randn(gen, hidden),
+    }
+    return {k: v.to(dtype).contiguous() for k, v in w.items()}
+
+
+def make_hidden(seq: int, hidden: int, seed: int, dtype: torch.dtype) -> torch.Tensor:
+    """Input hidden states x[seq, hidden] ~ N(0,1)."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed + 7919)
+    return _randn(gen, seq, hidden).to(dtype).contiguous()
+
+
+def make_workload_inputs(w: Workload, seed: int = 0, layer: int = 0):
+    """(x, weights) for one layer of a named workload; layer l uses seed 1000*seed + l."""
+    weights = make_layer(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn,
+                         1000 * seed + layer, w.torch_dtype)
+    x = make_hidden(w.seq, w.hidden, seed, w.torch_dtype)
+    return x, weights
+
+
+def make_qkv_cache(tc: int, kv_len: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                   seed: int, dtype: torch.dtype):
+    """Random q[tc, nq, d], k[kv_len, nkv, d], v[kv_len, nkv, d] for attention-only tests."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    q = _randn(gen, tc, n_q_heads, head_dim).to(dtype)
+    k = _randn(gen, kv_len, n_kv_heads, head_dim).to(dtype)
+    v = _randn(gen, kv_len, n_kv_heads, head_dim).to(dtype)
+    return q.contiguous(), k.contiguous(), v.contiguous()
+
+
+def sample_rows(seq: int, split: int, n: int, seed: int = 0):
+    """Row set for sampled parity at full sizes: chunk edges plus uniform draws, half per chunk."""
+    fixed = {0, 1, seq - 1}
+    if 0 < split < seq:
+        fixed |= {split - 1, split, min(split + 1, seq - 1)}
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed + 104729)
+    rows = set(r for r in fixed if 0 <= r < seq)
+    s = split if 0 < split < seq else seq // 2
+    while len(rows) < min(n, seq):
+        lo, hi = (0, s) if len(rows) % 2 == 0 else (s, seq)
+        if hi <= lo:
+            lo, hi = 0, seq
+        rows.add(int(torch.randint(lo, hi, (1,), generator=gen)))
+    return sorted(rows)
