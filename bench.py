@@ -1,0 +1,233 @@
+"""Benchmark of the ISO layer-shard prefill on one MI355X.
+
+A step is one pass of the whole hot path -- one decoder-layer shard over one synthetic prompt, cut into two
+chunks, chunk 0 on stream 0 and chunk 1 on stream 1, with the device-to-host copy standing in for the
+all-reduce at both communication points -- through libiso's C ABI.  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--split S] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="30b_tp4_2k")
+    ap.add_argument("--split", type=int, default=-1, help="split point (default: the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding across GPUs); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import iso_inputs
+    import paper_2409_11155_amd as iso
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = iso_inputs.WORKLOADS[args.workload]
+    T = wl.seq
+    split = wl.split if args.split < 0 else args.split
+    x_cpu, w_cpu = iso_inputs.make_workload_inputs(wl, seed=0)
+    w = {k: v.to(dev) for k, v in w_cpu.items()}
+    x0 = x_cpu.to(dev)
+    x = x0.clone()
+    kc = torch.zeros(T, wl.n_kv_heads, wl.head_dim, dtype=wl.torch_dtype, device=dev)
+    vc = torch.zeros_like(kc)
+    cfg = iso.make_cfg(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.dtype, T)
+    s0, s1 = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+    ctx = iso.Context(cfg, s0, s1)
+    K, W = args.steps, args.warmup
+
+    def run(n, sp, comm, sched):
+        for _ in range(n):
+            ctx.layer_prefill(w, x, kc, vc, T, sp, comm, sched)
+
+    def timed(sp, comm, sched):
+        """W warm-up steps, then exactly K steps between two full synchronisations; ms per step."""
+        x.copy_(x0)
+        run(W, sp, comm, sched)
+        ctx.sync()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(K, sp, comm, sched)
+        ctx.sync()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / K
+
+    D2H, NONE = iso.ISO_COMM_D2H, iso.ISO_COMM_NONE
+    OVL, SER = iso.ISO_SCHED_OVERLAP, iso.ISO_SCHED_SERIAL
+    t_iso = timed(split, D2H, OVL)                 # the headline: ISO schedule with the copy stand-in
+    t_serial = timed(split, D2H, SER)              # same chunks, one stream: compute + copies back to back
+    t_unsplit = timed(0, D2H, SER)                 # the pipeline ISO is compared with
+    t_iso_nocomm = timed(split, NONE, OVL)
+    t_unsplit_nocomm = timed(0, NONE, SER)
+
+    # ---- per-kernel durations, measured live with HIP events in the launch streams ----------------
+    def kinds(sp, comm, sched, steps):
+        x.copy_(x0)
+        run(2, sp, comm, sched)
+        ctx.sync()
+        ctx.timing_enable(True)
+        run(steps, sp, comm, sched)
+        out = ctx.timing_read()
+        ctx.timing_enable(False)
+        return {k: (ms / steps, n // steps) for k, (ms, n) in out.items()}
+
+    ksteps = max(1, min(K, 20))
+    k_iso = kinds(split, D2H, OVL, ksteps)           # as scheduled in the timed ISO steps
+    k_alone = kinds(split, NONE, SER, ksteps)        # same launches, one stream, nothing concurrent
+    k_comm = kinds(split, D2H, SER, ksteps)
+
+    H, F, d, nq = wl.hidden, wl.ffn, wl.head_dim, wl.n_q_heads
+    gemm_flops_tok = {"gemm_qkv": 2.0 * H * wl.n_qkv, "gemm_o": 2.0 * nq * d * H, "gemm_gate_up": 4.0 * H * F,
+                      "gemm_down": 2.0 * F * H}
+    two = 0 < split < T
+    attn_flops = (wl.attn_flops(0, split) + wl.attn_flops(split, T - split)) if two else wl.attn_flops(0, T)
+    e = 2 if wl.dtype == "bf16" else 4
+    nkv = wl.n_kv_heads
+    bytes_tok = {"rmsnorm": 2 * H * e, "resid_norm": 4 * H * e, "residual": 3 * H * e,
+                 "rope_kv": (2 * (nq + nkv) * d + 2 * nkv * d) * e, "swiglu": 3 * F * e}
+
+    def per_kernel(kd):
+        out = {}
+        for name, fl in gemm_flops_tok.items():
+            ms, n = kd[name]
+            if n:
+                out[name] = {"ms": ms, "launches": n, "tflops": fl * T / (ms * 1e-3) / 1e12}
+        ms, n = kd["attn"]
+        if n:
+            out["attn"] = {"ms": ms, "launches": n, "tflops": attn_flops / (ms * 1e-3) / 1e12}
+        for name, b in bytes_tok.items():
+            ms, n = kd[name]
+            if n:
+                out[name] = {"ms": ms, "launches": n, "gbs": b * T / (ms * 1e-3) / 1e9}
+        ms, n = kd["comm"]
+        if n:
+            out["comm"] = {"ms": ms, "launches": n, "gbs": 2.0 * T * H * e / (ms * 1e-3) / 1e9}
+        return out
+
+    pk_iso, pk_alone = per_kernel(k_iso), per_kernel(k_alone)
+    gemm_names = list(gemm_flops_tok)
+    bf16 = wl.dtype == "bf16"
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+
+    def gemm_roofline(kd):
+        ms = sum(kd[n][0] for n in gemm_names)
+        launches = sum(kd[n][1] for n in gemm_names)
+        flops = sum(gemm_flops_tok.values()) * T
+        return flops / (ms * 1e-3) / 1e12, ms / launches, flops / launches
+
+    ach, avg_ms, flops_per_launch = gemm_roofline(k_iso)
+    ach_alone, avg_ms_alone, _ = gemm_roofline(k_alone)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            with open(tpath) as f:
+                traffic = json.load(f).get(args.workload, {}).get("gemm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "mfma" if bf16 else "alu", "kernel": "gemm_bf16_mfma_kernel" if bf16 else "gemm_simple_kernel",
+                "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
+                "avg_launch_ms": avg_ms, "flops_per_launch": flops_per_launch,
+                "achieved_alone": ach_alone, "frac_alone": ach_alone / peak, "avg_launch_ms_alone": avg_ms_alone}
+
+    sum_x = k_comm["comm"][0]                                   # all copies of a step, back to back
+    sum_c = t_serial - sum_x if t_serial > sum_x else sum(v[0] for k, v in k_alone.items() if k != "comm")
+    hideable = min(sum_x, sum_c)
+    overlap = {
+        "t_iso_ms": t_iso, "t_split_serial_ms": t_serial, "t_unsplit_ms": t_unsplit,
+        "t_iso_nocomm_ms": t_iso_nocomm, "t_unsplit_nocomm_ms": t_unsplit_nocomm,
+        "reduction_vs_unsplit": 1.0 - t_iso / t_unsplit,
+        "iso_over_unsplit": t_iso / t_unsplit,
+        "sum_copy_ms": sum_x, "sum_compute_ms": sum_c,
+        "hidden_raw": (t_serial - t_iso) / sum_x if sum_x > 0 else None,
+        "hidden_of_hideable": (t_serial - t_iso) / hideable if hideable > 0 else None,
+    }
+
+    # ---- the oracle on the host cores, bounded ---------------------------------------------------
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = time_oracle(wl, x_cpu, w_cpu, split)
+
+    layer_flops = wl.gemm_flops() + attn_flops
+    result = {
+        "metric": "prefill tokens/s per layer shard (ISO vs unsplit) + attn/GEMM % MFMA peak",
+        "value": T / (t_iso * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": t_iso, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "hidden": H, "n_q_heads": nq, "n_kv_heads": nkv, "head_dim": d, "ffn": F,
+                   "seq": T, "split": split, "layers": 1, "comm": "d2h copy of [Tc,hidden] at both points",
+                   "schedule": "two streams, chunk per stream"},
+        "tflops": layer_flops / (t_iso * 1e-3) / 1e12,
+        "tflops_compute_only": layer_flops / (t_iso_nocomm * 1e-3) / 1e12,
+        "unsplit_tokens_per_s": T / (t_unsplit * 1e-3),
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "overlap": overlap,
+        "kernels_in_iso_schedule": pk_iso,
+        "kernels_alone": pk_alone,
+    }
+    ctx.close()
+    print(json.dumps(result))
+    return 0
+
+
+def time_oracle(wl, x_cpu, w_cpu, split):
+    """Times the CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import iso_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    sh = orc.LayerShape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.rms_eps, wl.rope_base)
+    wn = {k: v.to(torch.float64).numpy() for k, v in w_cpu.items()}
+    xn = x_cpu.to(torch.float64).numpy()
+    if wl.layer_flops() <= 1.0e12:
+        t0 = time.perf_counter()
+        orc.layer_unsplit(xn, wn, sh)
+        dt = time.perf_counter() - t0
+        return {"value": wl.seq / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                "sample": f"full layer, all {wl.seq} tokens, layer_unsplit in float64 numpy ({dt:.1f} s)"}
+    rows = 256
+    t0 = time.perf_counter()
+    orc.layer_rows(xn, wn, sh, list(range(0, wl.seq, wl.seq // rows))[:rows])
+    dt = time.perf_counter() - t0
+    # K/V for all tokens is a fixed cost; the rest scales with the number of rows
+    return {"value": rows / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"layer_rows on {rows} evenly spaced output rows of {wl.seq} (K/V computed for all tokens), "
+                      f"{dt:.1f} s; value = sampled rows per second, a lower bound on full-layer tokens/s"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,190 @@
+/*
+ * iso.h -- C ABI of the ISO (intra-sequence overlap) layer-shard prefill for MI355X (gfx950).
+ *
+ * One GPU's tensor-parallel shard of a decoder layer is run over one prompt that is cut into two
+ * chunks along the sequence (paper, Section 1 and Section 3.1).  The attention of chunk 1 reads the
+ * K/V rows that chunk 0 wrote to the cache; that is the only ordering constraint between the chunks
+ * (Section 3.1).  Everything else is per token and is issued per chunk on two HIP streams, so the
+ * communication point that ends each block (Section 2.2: the collective after o_proj and after the
+ * down matrix) overlaps with the other chunk's kernels.  On a single GPU the collective is replaced
+ * by a device-to-host copy of the same byte count, placed in the chunk's stream.
+ *
+ * Conventions
+ *   - All device buffers are caller-owned, row-major, token-major, 16-byte aligned.
+ *   - "hidden" is the full model width; head counts and ffn are LOCAL to the shard (Section 2.1, TP).
+ *   - Streams are hipStream_t handles passed as void*; every call is asynchronous with respect to the
+ *     host and returns after enqueueing.  No entry point synchronises the device except iso_sync and
+ *     iso_destroy.
+ *   - Every function returns ISO_OK (0) or a negative iso_status.  Arguments are validated before any
+ *     device work is enqueued; nothing throws or aborts.  iso_last_error() describes the last failure
+ *     of the calling thread.
+ *   - The sum over tensor-parallel ranks is over a world of one rank: the shard's partial output is
+ *     what is added to the residual stream.
+ */
+#ifndef ISO_H_
+#define ISO_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ISO_OK = 0,
+    ISO_ERR_NULL = -1,      /* a required pointer is NULL                               */
+    ISO_ERR_SHAPE = -2,     /* a size is non-positive, misaligned or inconsistent       */
+    ISO_ERR_DTYPE = -3,     /* unknown element type                                     */
+    ISO_ERR_SPLIT = -4,     /* split point outside [0, T]                               */
+    ISO_ERR_WORKSPACE = -5, /* T (or kv_len, M) exceeds what the context was created for */
+    ISO_ERR_HIP = -6        /* a HIP runtime call failed (no device, out of memory, ...) */
+} iso_status;
+
+typedef enum { ISO_F32 = 0, ISO_BF16 = 1 } iso_dtype;
+
+/* What stands at the two communication points of a layer (after o_proj, after down). */
+typedef enum {
+    ISO_COMM_NONE = 0, /* nothing: compute only                                                      */
+    ISO_COMM_D2H = 1   /* copy the [Tc, hidden] partial to pinned host memory in the chunk's stream;  */
+                       /* the consumer kernel is behind the copy in stream order                      */
+} iso_comm;
+
+/* How the two chunks are issued (Section 1, Figure 1 (a) versus (d)). */
+typedef enum {
+    ISO_SCHED_OVERLAP = 0, /* chunk 0 on stream0, chunk 1 on stream1, one event: KV of chunk 0 written */
+    ISO_SCHED_SERIAL = 1   /* both chunks on stream0, one block after the other, copies in line        */
+} iso_sched;
+
+typedef struct {
+    int hidden;      /* H, multiple of 8                                         */
+    int n_q_heads;   /* local query heads                                        */
+    int n_kv_heads;  /* local key/value heads; divides n_q_heads                 */
+    int head_dim;    /* 64 or 128                                                */
+    int ffn;         /* local MLP width F, multiple of 8                         */
+    float rms_eps;   /* RMSNorm epsilon (inside the square root)                 */
+    float rope_base; /* rotary base; theta_i = base^(-2i/head_dim)               */
+    int dtype;       /* iso_dtype of every activation, weight and cache tensor   */
+    int max_seq;     /* largest T (and kv_len) any later call may use            */
+} iso_cfg;
+
+/* Device pointers to one layer shard's weights, all of cfg.dtype.  y = x W^T for every matrix. */
+typedef struct {
+    const void *w_qkv;     /* [(nq + 2 nkv) * d, hidden]; rows: q heads, then k heads, then v heads */
+    const void *w_o;       /* [hidden, nq * d]                                                      */
+    const void *w_gate_up; /* [2 * ffn, hidden]; rows: gate, then up                                */
+    const void *w_down;    /* [hidden, ffn]                                                         */
+    const void *g_attn;    /* [hidden] RMSNorm gain before the attention block                      */
+    const void *g_mlp;     /* [hidden] RMSNorm gain before the MLP block                            */
+} iso_weights;
+
+typedef struct iso_ctx iso_ctx;
+
+/* Chunk ranges and buffer sizes derived on the host (no device needed). */
+typedef struct {
+    int n_chunks;             /* 1 (unsplit) or 2                                   */
+    int q_offset[2];          /* first token of each chunk                          */
+    int n_tokens[2];          /* tokens of each chunk                               */
+    int kv_len[2];            /* keys visible to each chunk = q_offset + n_tokens   */
+    size_t comm_bytes[2];     /* bytes moved at EACH communication point of a chunk */
+    size_t workspace_bytes;   /* device workspace a context for cfg.max_seq holds   */
+} iso_plan;
+
+/* Checks a configuration; returns ISO_OK or the error iso_create would return for it.  Host only. */
+int iso_validate_cfg(const iso_cfg *cfg);
+
+/* Fills `out` with the chunk ranges for a prompt of T tokens cut at `split` (Section 3.1; an unequal
+ * cut is the remedy of Section 6 for the dearer second half).  split == 0 or split == T means one
+ * chunk.  Host only.  Errors: NULL, bad cfg, T < 1, T > max_seq (ISO_ERR_WORKSPACE), split outside
+ * [0, T] (ISO_ERR_SPLIT). */
+int iso_plan_chunks(const iso_cfg *cfg, int T, int split, iso_plan *out);
+
+/* Creates a context on the current HIP device: workspace for max_seq tokens, the rotary table
+ * (computed on the host in double, stored fp32), one event pair, and pinned host memory for the
+ * copy stand-in.  stream0/stream1 are the caller's two streams (stream1 may equal stream0; NULL is
+ * the default stream).  On failure *out is NULL. */
+int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1);
+int iso_destroy(iso_ctx *ctx);            /* synchronises both streams, frees everything it owns */
+int iso_sync(iso_ctx *ctx);               /* waits for both streams                               */
+const char *iso_last_error(void);         /* message for the calling thread's last failure        */
+
+/* One decoder-layer shard over a prompt of T tokens (Section 2.2 for the block structure, Section 3.1
+ * for the chunking):
+ *     x1 = x + o_proj(attention(rope(qkv(rmsnorm(x; g_attn)))));  x = x1 + down(swiglu(gate_up(rmsnorm(x1; g_mlp))))
+ * x        [T, hidden] device, read and overwritten with the layer output.
+ * k_cache  [max_seq, nkv, d] device; rows 0..T-1 are written (keys after RoPE).
+ * v_cache  [max_seq, nkv, d] device; rows 0..T-1 are written.
+ * split    0 or T: one chunk on stream0.  1..T-1: two chunks [0,split) and [split,T).
+ * comm     iso_comm; sched: iso_sched (ignored for one chunk).
+ * On entry stream1 is made to wait for the work already in stream0; on return stream0 waits for
+ * stream1, so the call behaves like one operation enqueued on stream0.
+ * Errors: NULL, ISO_ERR_WORKSPACE if T > max_seq, ISO_ERR_SPLIT, ISO_ERR_SHAPE if T < 1. */
+int iso_layer_prefill(iso_ctx *ctx, const iso_weights *w, void *x, void *k_cache, void *v_cache,
+                      int T, int split, int comm, int sched);
+
+/* A stack of n_layers such layers (Section 2.2: stacked transformer blocks).  layers[l] are the
+ * weights of layer l; k_caches/v_caches hold n_layers consecutive caches of [max_seq, nkv, d].
+ * The chunks stay on their streams across layers (no join between layers), so the communication
+ * of layer l overlaps the attention block of layer l+1 of the other chunk. */
+int iso_stack_prefill(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x,
+                      void *k_caches, void *v_caches, int T, int split, int comm, int sched);
+
+/* Attention of one chunk over the KV cache (Section 3.1; chunked prefill, Section 2.1).
+ * q        [Tc, nq, d] device, rotary embedding already applied.
+ * k_cache, v_cache  [>= kv_len, nkv, d] device.
+ * out      [Tc, nq * d] device.
+ * Key j is visible to local row i iff j <= q_offset + i and j < kv_len; softmax scale 1/sqrt(d);
+ * query head h reads kv head h / (nq / nkv).
+ * Errors: NULL, Tc < 1, q_offset < 0, kv_len < 1 (ISO_ERR_SHAPE), kv_len > max_seq or
+ * Tc > max_seq (ISO_ERR_WORKSPACE). */
+int iso_attn_chunk(iso_ctx *ctx, const void *q, const void *k_cache, const void *v_cache, void *out,
+                   int Tc, int q_offset, int kv_len, void *stream);
+
+/* Row-parallel projection and its communication point (Section 2.2: o_proj / down followed by a
+ * collective):  c[M, N] = a[M, K] * w[N, K]^T, then, if host_sink != NULL, an asynchronous copy of c
+ * (M*N elements) to host_sink in the same stream.  host_sink must be pinned host memory of at least
+ * M*N*sizeof(element) bytes.  K must be a multiple of 8 for bf16.
+ * Errors: NULL, non-positive or misaligned sizes (ISO_ERR_SHAPE). */
+int iso_gemm_rowpar(iso_ctx *ctx, const void *a, const void *w, void *c, int M, int N, int K,
+                    void *stream, void *host_sink);
+
+/* The element-wise steps of the layer, exposed for parity tests and per-kernel measurement.
+ * All pointers are device pointers of cfg.dtype; `stream` is a hipStream_t.                     */
+/* y[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g */
+int iso_rmsnorm(iso_ctx *ctx, const void *x, const void *g, void *y, int T, void *stream);
+/* x[t,:] += delta[t,:] (in place); if y != NULL also y[t,:] = rmsnorm(x[t,:]; g) */
+int iso_residual_rmsnorm(iso_ctx *ctx, void *x, const void *delta, const void *g, void *y, int T,
+                         void *stream);
+/* qkv [Tc, (nq+2nkv)*d]: rotates the q part in place at positions q_offset+i and writes rotated k
+ * and plain v to rows q_offset+i of the caches (rotate-half pairs (i, i+d/2)). */
+int iso_rope_kv_write(iso_ctx *ctx, void *qkv, void *k_cache, void *v_cache, int Tc, int q_offset,
+                      void *stream);
+/* a[t, f] = silu(gu[t, f]) * gu[t, ffn + f],  gu [T, 2*ffn] -> a [T, ffn] */
+int iso_swiglu(iso_ctx *ctx, const void *gu, void *a, int T, void *stream);
+
+/* Kernel selection, for tests and measurement.  Default 0 = the matrix-core kernels wherever the dtype
+ * and shapes allow.  The forced alternatives are complete HIP kernels as well (they are the fp32 path). */
+enum {
+    ISO_FLAG_SIMPLE_GEMM = 1, /* SIMT tile GEMM instead of the MFMA GEMM                  */
+    ISO_FLAG_SIMPLE_ATTN = 2  /* one-wave-per-row attention instead of the MFMA attention */
+};
+int iso_set_flags(iso_ctx *ctx, int flags);
+
+/* Per-launch timing for measurement.  While enabled, every kernel launch and every copy the library
+ * enqueues is bracketed by a pair of HIP events recorded in the stream of that launch (at most 8192
+ * launches are kept; enabling clears the record).  iso_timing_read synchronises both streams and returns
+ * the summed duration and the number of recorded launches of one kind. */
+typedef enum {
+    ISO_K_GEMM_QKV = 0, ISO_K_GEMM_O = 1, ISO_K_GEMM_GATE_UP = 2, ISO_K_GEMM_DOWN = 3, ISO_K_ATTN = 4,
+    ISO_K_RMSNORM = 5, ISO_K_RESID_NORM = 6, ISO_K_RESIDUAL = 7, ISO_K_ROPE_KV = 8, ISO_K_SWIGLU = 9,
+    ISO_K_COMM = 10, ISO_K_COUNT = 11
+} iso_kernel_kind;
+int iso_timing_enable(iso_ctx *ctx, int on);
+int iso_timing_read(iso_ctx *ctx, int kind, double *total_ms, int *launches);
+
+/* Pinned host buffer the context uses for ISO_COMM_D2H (2 * max_seq * hidden elements), for tests. */
+void *iso_host_sink(iso_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ISO_H_ */

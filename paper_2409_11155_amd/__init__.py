@@ -1,0 +1,233 @@
+"""Python binding of libiso: argument marshalling only.
+
+Every step of the ISO layer-shard prefill runs inside the HIP kernels of libiso.so; this module turns
+torch tensors and streams into the plain pointers and sizes of the C ABI (include/iso.h) and turns error
+codes into exceptions.  There is no fallback: if the library is missing, importing a binding function
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+from . import build as _build
+
+ISO_OK = 0
+ISO_ERR_NULL, ISO_ERR_SHAPE, ISO_ERR_DTYPE, ISO_ERR_SPLIT, ISO_ERR_WORKSPACE, ISO_ERR_HIP = -1, -2, -3, -4, -5, -6
+ISO_F32, ISO_BF16 = 0, 1
+ISO_COMM_NONE, ISO_COMM_D2H = 0, 1
+ISO_SCHED_OVERLAP, ISO_SCHED_SERIAL = 0, 1
+ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN = 1, 2
+
+EXPORTS = [
+    "iso_validate_cfg", "iso_plan_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",
+    "iso_layer_prefill", "iso_stack_prefill", "iso_attn_chunk", "iso_gemm_rowpar", "iso_rmsnorm",
+    "iso_residual_rmsnorm", "iso_rope_kv_write", "iso_swiglu", "iso_set_flags", "iso_host_sink",
+    "iso_timing_enable", "iso_timing_read",
+]
+KERNEL_KINDS = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn", "rmsnorm", "resid_norm", "residual",
+                "rope_kv", "swiglu", "comm"]
+
+
+class IsoCfg(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int), ("n_q_heads", ctypes.c_int), ("n_kv_heads", ctypes.c_int),
+                ("head_dim", ctypes.c_int), ("ffn", ctypes.c_int), ("rms_eps", ctypes.c_float),
+                ("rope_base", ctypes.c_float), ("dtype", ctypes.c_int), ("max_seq", ctypes.c_int)]
+
+
+class IsoWeights(ctypes.Structure):
+    _fields_ = [("w_qkv", ctypes.c_void_p), ("w_o", ctypes.c_void_p), ("w_gate_up", ctypes.c_void_p),
+                ("w_down", ctypes.c_void_p), ("g_attn", ctypes.c_void_p), ("g_mlp", ctypes.c_void_p)]
+
+
+class IsoPlan(ctypes.Structure):
+    _fields_ = [("n_chunks", ctypes.c_int), ("q_offset", ctypes.c_int * 2), ("n_tokens", ctypes.c_int * 2),
+                ("kv_len", ctypes.c_int * 2), ("comm_bytes", ctypes.c_size_t * 2),
+                ("workspace_bytes", ctypes.c_size_t)]
+
+
+class IsoError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libiso error {code}: {msg}")
+        self.code = code
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib_path() -> str:
+    return _build.LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Loads libiso.so (building it once if no built library is present)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build(verbose=False)
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.iso_last_error.restype = ctypes.c_char_p
+    lib.iso_last_error.argtypes = []
+    lib.iso_validate_cfg.argtypes = [ctypes.POINTER(IsoCfg)]
+    lib.iso_plan_chunks.argtypes = [ctypes.POINTER(IsoCfg), ci, ci, ctypes.POINTER(IsoPlan)]
+    lib.iso_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(IsoCfg), vp, vp]
+    lib.iso_destroy.argtypes = [vp]
+    lib.iso_sync.argtypes = [vp]
+    lib.iso_set_flags.argtypes = [vp, ci]
+    lib.iso_host_sink.argtypes = [vp]
+    lib.iso_host_sink.restype = vp
+    lib.iso_layer_prefill.argtypes = [vp, ctypes.POINTER(IsoWeights), vp, vp, vp, ci, ci, ci, ci]
+    lib.iso_stack_prefill.argtypes = [vp, ctypes.POINTER(IsoWeights), ci, vp, vp, vp, ci, ci, ci, ci]
+    lib.iso_attn_chunk.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp]
+    lib.iso_gemm_rowpar.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp, vp]
+    lib.iso_rmsnorm.argtypes = [vp, vp, vp, vp, ci, vp]
+    lib.iso_residual_rmsnorm.argtypes = [vp, vp, vp, vp, vp, ci, vp]
+    lib.iso_rope_kv_write.argtypes = [vp, vp, vp, vp, ci, ci, vp]
+    lib.iso_swiglu.argtypes = [vp, vp, vp, ci, vp]
+    lib.iso_timing_enable.argtypes = [vp, ci]
+    lib.iso_timing_read.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
+    for name in EXPORTS:
+        if name not in ("iso_last_error", "iso_host_sink"):
+            getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def last_error() -> str:
+    return load().iso_last_error().decode()
+
+
+def _check(code: int) -> None:
+    if code != ISO_OK:
+        raise IsoError(code, last_error())
+
+
+def make_cfg(hidden: int, n_q_heads: int, n_kv_heads: int, head_dim: int, ffn: int, dtype, max_seq: int,
+             rms_eps: float = 1e-6, rope_base: float = 10000.0) -> IsoCfg:
+    if isinstance(dtype, torch.dtype):
+        dtype = {torch.float32: ISO_F32, torch.bfloat16: ISO_BF16}[dtype]
+    elif isinstance(dtype, str):
+        dtype = {"f32": ISO_F32, "bf16": ISO_BF16}[dtype]
+    return IsoCfg(hidden, n_q_heads, n_kv_heads, head_dim, ffn, rms_eps, rope_base, int(dtype), max_seq)
+
+
+def validate_cfg(cfg: IsoCfg) -> int:
+    return load().iso_validate_cfg(ctypes.byref(cfg))
+
+
+def plan_chunks(cfg: IsoCfg, T: int, split: int) -> IsoPlan:
+    plan = IsoPlan()
+    _check(load().iso_plan_chunks(ctypes.byref(cfg), T, split, ctypes.byref(plan)))
+    return plan
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("libiso takes contiguous tensors")
+    return t.data_ptr()
+
+
+def _stream_handle(s) -> Optional[int]:
+    if s is None:
+        return None
+    if isinstance(s, torch.cuda.Stream):
+        return s.cuda_stream or None
+    return int(s) or None
+
+
+def pack_weights(w: Dict[str, torch.Tensor]) -> IsoWeights:
+    return IsoWeights(_ptr(w["w_qkv"]), _ptr(w["w_o"]), _ptr(w["w_gate_up"]), _ptr(w["w_down"]),
+                      _ptr(w["g_attn"]), _ptr(w["g_mlp"]))
+
+
+class Context:
+    """Owns an iso_ctx.  `stream0`/`stream1` are torch.cuda.Stream objects (or None for the default)."""
+
+    def __init__(self, cfg: IsoCfg, stream0=None, stream1=None):
+        self._lib = load()
+        self.cfg = cfg
+        self.stream0, self.stream1 = stream0, stream1   # keep the torch streams alive
+        handle = ctypes.c_void_p()
+        _check(self._lib.iso_create(ctypes.byref(handle), ctypes.byref(cfg), _stream_handle(stream0),
+                                    _stream_handle(stream1)))
+        self._h = handle
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            self._lib.iso_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    # ---- entry points (same names as the C ABI, without the prefix) ----------------------------
+    def sync(self) -> None:
+        _check(self._lib.iso_sync(self._h))
+
+    def set_flags(self, flags: int) -> None:
+        _check(self._lib.iso_set_flags(self._h, flags))
+
+    def timing_enable(self, on: bool) -> None:
+        _check(self._lib.iso_timing_enable(self._h, 1 if on else 0))
+
+    def timing_read(self) -> Dict[str, tuple]:
+        """{kind: (total_ms, launches)} for every kernel kind recorded since timing_enable(True)."""
+        out = {}
+        for i, name in enumerate(KERNEL_KINDS):
+            ms, n = ctypes.c_double(), ctypes.c_int()
+            _check(self._lib.iso_timing_read(self._h, i, ctypes.byref(ms), ctypes.byref(n)))
+            out[name] = (ms.value, n.value)
+        return out
+
+    def host_sink(self) -> int:
+        return self._lib.iso_host_sink(self._h)
+
+    def layer_prefill(self, w: Dict[str, torch.Tensor], x, k_cache, v_cache, T: int, split: int,
+                      comm: int = ISO_COMM_NONE, sched: int = ISO_SCHED_OVERLAP) -> None:
+        ws = pack_weights(w)
+        _check(self._lib.iso_layer_prefill(self._h, ctypes.byref(ws), _ptr(x), _ptr(k_cache), _ptr(v_cache),
+                                           T, split, comm, sched))
+
+    def stack_prefill(self, layers: Sequence[Dict[str, torch.Tensor]], x, k_caches, v_caches, T: int, split: int,
+                      comm: int = ISO_COMM_NONE, sched: int = ISO_SCHED_OVERLAP) -> None:
+        arr = (IsoWeights * len(layers))(*[pack_weights(w) for w in layers])
+        _check(self._lib.iso_stack_prefill(self._h, arr, len(layers), _ptr(x), _ptr(k_caches), _ptr(v_caches),
+                                           T, split, comm, sched))
+
+    def attn_chunk(self, q, k_cache, v_cache, out, Tc: int, q_offset: int, kv_len: int, stream=None) -> None:
+        _check(self._lib.iso_attn_chunk(self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), Tc, q_offset,
+                                        kv_len, _stream_handle(stream)))
+
+    def gemm_rowpar(self, a, w, c, M: int, N: int, K: int, stream=None, host_sink: Optional[int] = None) -> None:
+        _check(self._lib.iso_gemm_rowpar(self._h, _ptr(a), _ptr(w), _ptr(c), M, N, K, _stream_handle(stream),
+                                         host_sink))
+
+    def rmsnorm(self, x, g, y, T: int, stream=None) -> None:
+        _check(self._lib.iso_rmsnorm(self._h, _ptr(x), _ptr(g), _ptr(y), T, _stream_handle(stream)))
+
+    def residual_rmsnorm(self, x, delta, g, y, T: int, stream=None) -> None:
+        _check(self._lib.iso_residual_rmsnorm(self._h, _ptr(x), _ptr(delta), _ptr(g), _ptr(y), T,
+                                              _stream_handle(stream)))
+
+    def rope_kv_write(self, qkv, k_cache, v_cache, Tc: int, q_offset: int, stream=None) -> None:
+        _check(self._lib.iso_rope_kv_write(self._h, _ptr(qkv), _ptr(k_cache), _ptr(v_cache), Tc, q_offset,
+                                           _stream_handle(stream)))
+
+    def swiglu(self, gu, a, T: int, stream=None) -> None:
+        _check(self._lib.iso_swiglu(self._h, _ptr(gu), _ptr(a), T, _stream_handle(stream)))

@@ -1,0 +1,212 @@
+// Bandwidth-bound steps of the layer: RMSNorm (optionally fused with the residual add), rotary
+// embedding + KV-cache write, SwiGLU.  Each kernel moves every byte once with 16-byte accesses and
+// does its arithmetic in fp32.  (Layer structure: paper Section 2.2; KV-cache write before the next
+// chunk's attention: Section 3.1.)
+#include "iso_internal.h"
+
+namespace {
+
+template <typename T> struct Vec16 {
+    static constexpr int N = 16 / sizeof(T);
+    T v[N];
+};
+
+template <typename T> __device__ __forceinline__ void load16(const T *p, float (&out)[16 / sizeof(T)]) {
+    uint4 raw = *reinterpret_cast<const uint4 *>(p);
+    const T *e = reinterpret_cast<const T *>(&raw);
+#pragma unroll
+    for (int i = 0; i < (int)(16 / sizeof(T)); ++i) out[i] = iso_to_f32(e[i]);
+}
+
+template <typename T> __device__ __forceinline__ void store16(T *p, const float (&in)[16 / sizeof(T)]) {
+    uint4 raw;
+    T *e = reinterpret_cast<T *>(&raw);
+#pragma unroll
+    for (int i = 0; i < (int)(16 / sizeof(T)); ++i) e[i] = iso_from_f32<T>(in[i]);
+    *reinterpret_cast<uint4 *>(p) = raw;
+}
+
+// One 256-thread workgroup per token row.  x_new = x (+ delta); optionally written back; optionally
+// y = x_new * rsqrt(mean(x_new^2) + eps) * g.  The first CACHE vectors of each thread stay in
+// registers between the reduction and the scaling, so rows up to 256*CACHE*VEC elements are read once.
+template <typename T, bool HAS_DELTA, bool WRITE_Y>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const T *__restrict__ delta,
+                                                      T *x_out, const T *__restrict__ g, T *__restrict__ y,
+                                                      int H, float eps) {
+    constexpr int VEC = 16 / sizeof(T);
+    constexpr int CACHE = 4;
+    const int tid = threadIdx.x;
+    const int nvec = H / VEC;
+    const size_t row = (size_t)blockIdx.x * H;
+    float vals[CACHE][VEC];
+    float ss = 0.f;
+#pragma unroll
+    for (int c = 0; c < CACHE; ++c) {
+        const int idx = tid + c * 256;
+        if (idx < nvec) {
+            load16<T>(x + row + (size_t)idx * VEC, vals[c]);
+            if (HAS_DELTA) {
+                float dv[VEC];
+                load16<T>(delta + row + (size_t)idx * VEC, dv);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) vals[c][i] += dv[i];
+                store16<T>(x_out + row + (size_t)idx * VEC, vals[c]);
+            }
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) ss += vals[c][i] * vals[c][i];
+        }
+    }
+    for (int idx = tid + CACHE * 256; idx < nvec; idx += 256) {
+        float xv[VEC];
+        load16<T>(x + row + (size_t)idx * VEC, xv);
+        if (HAS_DELTA) {
+            float dv[VEC];
+            load16<T>(delta + row + (size_t)idx * VEC, dv);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) xv[i] += dv[i];
+            store16<T>(x_out + row + (size_t)idx * VEC, xv);
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) ss += xv[i] * xv[i];
+    }
+    if (!WRITE_Y) return;
+
+    __shared__ float red[4];
+    ss = iso_wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float total = red[0] + red[1] + red[2] + red[3];
+    const float scale = 1.0f / sqrtf(total / (float)H + eps);
+
+#pragma unroll
+    for (int c = 0; c < CACHE; ++c) {
+        const int idx = tid + c * 256;
+        if (idx < nvec) {
+            float gv[VEC];
+            load16<T>(g + (size_t)idx * VEC, gv);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) gv[i] = vals[c][i] * scale * gv[i];
+            store16<T>(y + row + (size_t)idx * VEC, gv);
+        }
+    }
+    for (int idx = tid + CACHE * 256; idx < nvec; idx += 256) {
+        // beyond the register cache: re-read the (already updated) row
+        float xv[VEC], gv[VEC];
+        load16<T>((HAS_DELTA ? (const T *)x_out : x) + row + (size_t)idx * VEC, xv);
+        load16<T>(g + (size_t)idx * VEC, gv);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) gv[i] = xv[i] * scale * gv[i];
+        store16<T>(y + row + (size_t)idx * VEC, gv);
+    }
+}
+
+// One workgroup per token.  Work units of 16 bytes: (head, slice of the low half) for the rotation of
+// q and k heads, then plain 16-byte copies for v.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kv_kernel(T *qkv, T *__restrict__ k_cache, T *__restrict__ v_cache,
+                                                      const float *__restrict__ cos_t,
+                                                      const float *__restrict__ sin_t, int q_offset, int nq,
+                                                      int nkv, int d) {
+    constexpr int VEC = 16 / sizeof(T);
+    const int t = blockIdx.x;
+    const int pos = q_offset + t;
+    const int half = d / 2;
+    const int upr = half / VEC;
+    const int n_rot = (nq + nkv) * upr;
+    const int n_v = nkv * d / VEC;
+    T *row = qkv + (size_t)t * (nq + 2 * nkv) * d;
+    for (int u = threadIdx.x; u < n_rot + n_v; u += 256) {
+        if (u < n_rot) {
+            const int head = u / upr;
+            const int i0 = (u % upr) * VEC;
+            T *lo_p = row + (size_t)head * d + i0;
+            float lo[VEC], hi[VEC], olo[VEC], ohi[VEC];
+            load16<T>(lo_p, lo);
+            load16<T>(lo_p + half, hi);
+            const float *cp = cos_t + (size_t)pos * half + i0;
+            const float *sp = sin_t + (size_t)pos * half + i0;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                const float c = cp[i], s = sp[i];
+                olo[i] = lo[i] * c - hi[i] * s;
+                ohi[i] = hi[i] * c + lo[i] * s;
+            }
+            T *dst = (head < nq) ? lo_p : k_cache + ((size_t)pos * nkv + (head - nq)) * d + i0;
+            store16<T>(dst, olo);
+            store16<T>(dst + half, ohi);
+        } else {
+            const int uu = u - n_rot;
+            const uint4 raw = *reinterpret_cast<const uint4 *>(row + (size_t)(nq + nkv) * d + (size_t)uu * VEC);
+            *reinterpret_cast<uint4 *>(v_cache + (size_t)pos * nkv * d + (size_t)uu * VEC) = raw;
+        }
+    }
+}
+
+template <typename T> __device__ __forceinline__ float silu_f(float z);
+template <> __device__ __forceinline__ float silu_f<float>(float z) { return z / (1.0f + expf(-z)); }
+template <> __device__ __forceinline__ float silu_f<bf16_t>(float z) { return z / (1.0f + __expf(-z)); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_kernel(const T *__restrict__ gu, T *__restrict__ a, size_t n_units,
+                                                     int F) {
+    constexpr int VEC = 16 / sizeof(T);
+    const int upr = F / VEC;
+    for (size_t u = (size_t)blockIdx.x * 256 + threadIdx.x; u < n_units; u += (size_t)gridDim.x * 256) {
+        const size_t t = u / upr;
+        const int f0 = (int)(u % upr) * VEC;
+        float gate[VEC], up[VEC];
+        load16<T>(gu + t * 2 * F + f0, gate);
+        load16<T>(gu + t * 2 * F + F + f0, up);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) gate[i] = silu_f<T>(gate[i]) * up[i];
+        store16<T>(a + t * F + f0, gate);
+    }
+}
+
+template <typename T>
+hipError_t rmsnorm_dispatch(const void *x, const void *delta, void *x_out, const void *g, void *y, int T_, int H,
+                            float eps, hipStream_t s) {
+    dim3 grid(T_), block(256);
+    const T *xp = (const T *)x;
+    const T *dp = (const T *)delta;
+    if (delta && y)
+        hipLaunchKernelGGL((rmsnorm_kernel<T, true, true>), grid, block, 0, s, xp, dp, (T *)x_out, (const T *)g, (T *)y, H, eps);
+    else if (delta)
+        hipLaunchKernelGGL((rmsnorm_kernel<T, true, false>), grid, block, 0, s, xp, dp, (T *)x_out, (const T *)g, (T *)y, H, eps);
+    else
+        hipLaunchKernelGGL((rmsnorm_kernel<T, false, true>), grid, block, 0, s, xp, dp, (T *)x_out, (const T *)g, (T *)y, H, eps);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta, void *x_out, const void *g, void *y,
+                              int T, int H, float eps, hipStream_t s) {
+    if (dtype == ISO_F32) return rmsnorm_dispatch<float>(x, delta, x_out, g, y, T, H, eps, s);
+    return rmsnorm_dispatch<bf16_t>(x, delta, x_out, g, y, T, H, eps, s);
+}
+
+hipError_t iso_launch_rope_kv(int dtype, void *qkv, void *k_cache, void *v_cache, const float *cos_t,
+                              const float *sin_t, int Tc, int q_offset, int nq, int nkv, int d, hipStream_t s) {
+    dim3 grid(Tc), block(256);
+    if (dtype == ISO_F32)
+        hipLaunchKernelGGL(rope_kv_kernel<float>, grid, block, 0, s, (float *)qkv, (float *)k_cache,
+                           (float *)v_cache, cos_t, sin_t, q_offset, nq, nkv, d);
+    else
+        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, grid, block, 0, s, (bf16_t *)qkv, (bf16_t *)k_cache,
+                           (bf16_t *)v_cache, cos_t, sin_t, q_offset, nq, nkv, d);
+    return hipGetLastError();
+}
+
+hipError_t iso_launch_swiglu(int dtype, const void *gu, void *a, int T, int F, hipStream_t s) {
+    const size_t vec = dtype == ISO_F32 ? 4 : 8;
+    const size_t n_units = (size_t)T * (F / vec);
+    size_t blocks = (n_units + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    dim3 grid((unsigned)blocks), block(256);
+    if (dtype == ISO_F32)
+        hipLaunchKernelGGL(swiglu_kernel<float>, grid, block, 0, s, (const float *)gu, (float *)a, n_units, F);
+    else
+        hipLaunchKernelGGL(swiglu_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)gu, (bf16_t *)a, n_units, F);
+    return hipGetLastError();
+}

@@ -1,0 +1,498 @@
+// C ABI of libiso: argument validation, context, and the two-stream ISO schedule.
+//
+// Schedule (paper Section 1, Figure 1(d); Section 3.1).  A layer is two blocks per chunk: the attention
+// block A (norm, QKV, RoPE + cache write, attention, o_proj) and the MLP block M (residual + norm,
+// gate/up, SwiGLU, down), each ending in a communication point X.  Chunk c's kernels AND its two copies
+// are enqueued on stream c, so "the consumer of a collective waits for it" is plain stream order, and
+// while stream c is inside a copy the other stream's kernels own the compute units.  The single
+// cross-stream dependency is the event "chunk 0 has written its K/V rows", awaited by chunk 1 right
+// before its attention (Section 3.1).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "iso_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));    \
+    } while (0)
+
+size_t elt_size(int dtype) { return dtype == ISO_F32 ? 4 : 2; }
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int n_qkv(const iso_cfg &c) { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
+
+struct WsLayout {
+    size_t y, qkv, attn, part, gu, act, total;
+};
+
+WsLayout ws_layout(const iso_cfg &c) {
+    const size_t e = elt_size(c.dtype), t = (size_t)c.max_seq;
+    WsLayout l;
+    size_t off = 0;
+    auto take = [&](size_t elems) { size_t o = off; off = align_up(off + elems * e, 256); return o; };
+    l.y = take(t * c.hidden);
+    l.qkv = take(t * n_qkv(c));
+    l.attn = take(t * c.n_q_heads * c.head_dim);
+    l.part = take(t * c.hidden);
+    l.gu = take(t * 2 * c.ffn);
+    l.act = take(t * c.ffn);
+    l.total = off;
+    return l;
+}
+
+int check_cfg(const iso_cfg *c) {
+    if (!c) return fail(ISO_ERR_NULL, "cfg is NULL");
+    if (c->dtype != ISO_F32 && c->dtype != ISO_BF16) return fail(ISO_ERR_DTYPE, "dtype %d is not ISO_F32/ISO_BF16", c->dtype);
+    if (c->hidden < 8 || c->hidden % 8) return fail(ISO_ERR_SHAPE, "hidden=%d must be a positive multiple of 8", c->hidden);
+    if (c->ffn < 8 || c->ffn % 8) return fail(ISO_ERR_SHAPE, "ffn=%d must be a positive multiple of 8", c->ffn);
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(ISO_ERR_SHAPE, "head_dim=%d must be 64 or 128", c->head_dim);
+    if (c->n_q_heads < 1 || c->n_kv_heads < 1) return fail(ISO_ERR_SHAPE, "head counts must be positive");
+    if (c->n_q_heads % c->n_kv_heads) return fail(ISO_ERR_SHAPE, "n_q_heads=%d is not a multiple of n_kv_heads=%d", c->n_q_heads, c->n_kv_heads);
+    if (c->max_seq < 1) return fail(ISO_ERR_SHAPE, "max_seq=%d must be positive", c->max_seq);
+    if (!(c->rms_eps >= 0.f)) return fail(ISO_ERR_SHAPE, "rms_eps must be >= 0");
+    if (!(c->rope_base > 1.f)) return fail(ISO_ERR_SHAPE, "rope_base must be > 1");
+    return ISO_OK;
+}
+
+// Brackets one launch with a pair of events in the launch's own stream when timing is on.
+struct Timed {
+    iso_ctx *c;
+    int idx;
+    hipStream_t s;
+    Timed(iso_ctx *ctx, int kind, hipStream_t stream) : c(ctx), idx(-1), s(stream) {
+        if (!c->timing || c->n_tev >= ISO_MAX_TIMED) return;
+        if (c->n_tev == c->n_tev_created) {
+            if (hipEventCreate(&c->tev0[c->n_tev]) != hipSuccess) return;
+            if (hipEventCreate(&c->tev1[c->n_tev]) != hipSuccess) { (void)hipEventDestroy(c->tev0[c->n_tev]); return; }
+            c->n_tev_created++;
+        }
+        idx = c->n_tev++;
+        c->tkind[idx] = kind;
+        (void)hipEventRecord(c->tev0[idx], s);
+    }
+    ~Timed() {
+        if (idx >= 0) (void)hipEventRecord(c->tev1[idx], s);
+    }
+};
+
+inline char *at(void *base, size_t row, size_t width, size_t e) { return (char *)base + row * width * e; }
+inline const char *at(const void *base, size_t row, size_t width, size_t e) { return (const char *)base + row * width * e; }
+
+int gemm(iso_ctx *ctx, int kind, const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
+    Timed t_(ctx, kind, s);
+    hipError_t e;
+    if (ctx->cfg.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_GEMM) && iso_gemm_bf16_mfma_supported(M, N, K))
+        e = iso_launch_gemm_bf16_mfma(a, w, c, M, N, K, s);
+    else
+        e = iso_launch_gemm_simple(ctx->cfg.dtype, a, w, c, M, N, K, s);
+    if (e != hipSuccess) return fail(ISO_ERR_HIP, "gemm launch (M=%d N=%d K=%d): %s", M, N, K, hipGetErrorString(e));
+    return ISO_OK;
+}
+
+int attention(iso_ctx *ctx, const void *q, int q_stride, const void *kc, const void *vc, void *out, int Tc,
+              int q_offset, int kv_len, hipStream_t s) {
+    const iso_cfg &c = ctx->cfg;
+    Timed t_(ctx, ISO_K_ATTN, s);
+    hipError_t e;
+    if (c.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_ATTN) && iso_attn_bf16_mfma_supported(c.head_dim))
+        e = iso_launch_attn_bf16_mfma(q, kc, vc, out, Tc, q_offset, kv_len, c.n_q_heads, c.n_kv_heads, c.head_dim, q_stride, s);
+    else
+        e = iso_launch_attn_simple(c.dtype, q, kc, vc, out, Tc, q_offset, kv_len, c.n_q_heads, c.n_kv_heads, c.head_dim, q_stride, s);
+    if (e != hipSuccess) return fail(ISO_ERR_HIP, "attention launch: %s", hipGetErrorString(e));
+    return ISO_OK;
+}
+
+#define ISO_TRY(expr)              \
+    do {                           \
+        int r_ = (expr);           \
+        if (r_ != ISO_OK) return r_; \
+    } while (0)
+
+#define LAUNCH_TRY(kind, stream, expr, what)                                                       \
+    do {                                                                                           \
+        Timed t_(ctx, kind, stream);                                                               \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "%s launch: %s", what, hipGetErrorString(e_)); \
+    } while (0)
+
+// One chunk = token rows [lo, lo + n).
+struct Chunk {
+    int lo, n;
+    hipStream_t s;
+};
+
+// Attention block of one chunk.  `first_norm_delta`: when not NULL the block starts with the residual add
+// left over from the previous layer's MLP block (x += delta) fused into this norm.
+int attn_block_head(iso_ctx *ctx, const iso_weights *w, void *x, void *kc, void *vc, const Chunk &ck,
+                    bool add_prev_partial) {
+    const iso_cfg &c = ctx->cfg;
+    const size_t e = ctx->elt;
+    const int H = c.hidden, NQKV = n_qkv(c);
+    char *xr = at(x, ck.lo, H, e);
+    char *yr = at(ctx->y, ck.lo, H, e);
+    char *qkvr = at(ctx->qkv, ck.lo, NQKV, e);
+    if (add_prev_partial)
+        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, at(ctx->part, ck.lo, H, e), xr, w->g_attn, yr, ck.n, H, c.rms_eps, ck.s), "residual+rmsnorm");
+    else
+        LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, nullptr, nullptr, w->g_attn, yr, ck.n, H, c.rms_eps, ck.s), "rmsnorm");
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_QKV, yr, w->w_qkv, qkvr, ck.n, NQKV, H, ck.s));
+    LAUNCH_TRY(ISO_K_ROPE_KV, ck.s, iso_launch_rope_kv(c.dtype, qkvr, kc, vc, ctx->rope_cos, ctx->rope_sin, ck.n, ck.lo, c.n_q_heads,
+                                  c.n_kv_heads, c.head_dim, ck.s), "rope+kv");
+    return ISO_OK;
+}
+
+int attn_block_tail(iso_ctx *ctx, const iso_weights *w, void *kc, void *vc, const Chunk &ck, int comm) {
+    const iso_cfg &c = ctx->cfg;
+    const size_t e = ctx->elt;
+    const int H = c.hidden, NQKV = n_qkv(c), NQD = c.n_q_heads * c.head_dim;
+    char *qkvr = at(ctx->qkv, ck.lo, NQKV, e);
+    char *attnr = at(ctx->attn, ck.lo, NQD, e);
+    char *partr = at(ctx->part, ck.lo, H, e);
+    ISO_TRY(attention(ctx, qkvr, NQKV, kc, vc, attnr, ck.n, ck.lo, ck.lo + ck.n, ck.s));
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_O, attnr, w->w_o, partr, ck.n, H, NQD, ck.s));
+    if (comm == ISO_COMM_D2H) {
+        Timed t_(ctx, ISO_K_COMM, ck.s);
+        HIP_TRY(hipMemcpyAsync(at(ctx->host_sink, ck.lo, H, e), partr, (size_t)ck.n * H * e, hipMemcpyDeviceToHost, ck.s));
+    }
+    return ISO_OK;
+}
+
+int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int comm) {
+    const iso_cfg &c = ctx->cfg;
+    const size_t e = ctx->elt;
+    const int H = c.hidden, F = c.ffn;
+    char *xr = at(x, ck.lo, H, e);
+    char *yr = at(ctx->y, ck.lo, H, e);
+    char *partr = at(ctx->part, ck.lo, H, e);
+    char *gur = at(ctx->gu, ck.lo, 2 * (size_t)F, e);
+    char *actr = at(ctx->act, ck.lo, F, e);
+    LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, partr, xr, w->g_mlp, yr, ck.n, H, c.rms_eps, ck.s), "residual+rmsnorm");
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_GATE_UP, yr, w->w_gate_up, gur, ck.n, 2 * F, H, ck.s));
+    LAUNCH_TRY(ISO_K_SWIGLU, ck.s, iso_launch_swiglu(c.dtype, gur, actr, ck.n, F, ck.s), "swiglu");
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_DOWN, actr, w->w_down, partr, ck.n, H, F, ck.s));
+    if (comm == ISO_COMM_D2H) {
+        Timed t_(ctx, ISO_K_COMM, ck.s);
+        HIP_TRY(hipMemcpyAsync(at((char *)ctx->host_sink + (size_t)c.max_seq * H * e, ck.lo, H, e), partr,
+                               (size_t)ck.n * H * e, hipMemcpyDeviceToHost, ck.s));
+    }
+    return ISO_OK;
+}
+
+int final_residual(iso_ctx *ctx, void *x, const Chunk &ck) {
+    const iso_cfg &c = ctx->cfg;
+    const size_t e = ctx->elt;
+    char *xr = at(x, ck.lo, c.hidden, e);
+    LAUNCH_TRY(ISO_K_RESIDUAL, ck.s, iso_launch_rmsnorm(c.dtype, xr, at(ctx->part, ck.lo, c.hidden, e), xr, nullptr, nullptr, ck.n, c.hidden,
+                                  c.rms_eps, ck.s), "residual");
+    return ISO_OK;
+}
+
+int check_layer_args(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, void *kc, void *vc, int T,
+                     int split, int comm, int sched) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!layers || !x || !kc || !vc) return fail(ISO_ERR_NULL, "weights, x, k_cache and v_cache must be non-NULL");
+    if (n_layers < 1) return fail(ISO_ERR_SHAPE, "n_layers=%d must be positive", n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        const iso_weights &w = layers[l];
+        if (!w.w_qkv || !w.w_o || !w.w_gate_up || !w.w_down || !w.g_attn || !w.g_mlp)
+            return fail(ISO_ERR_NULL, "layer %d has a NULL weight pointer", l);
+    }
+    if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
+    if (T > ctx->cfg.max_seq) return fail(ISO_ERR_WORKSPACE, "T=%d exceeds max_seq=%d", T, ctx->cfg.max_seq);
+    if (split < 0 || split > T) return fail(ISO_ERR_SPLIT, "split=%d outside [0, %d]", split, T);
+    if (comm != ISO_COMM_NONE && comm != ISO_COMM_D2H) return fail(ISO_ERR_SHAPE, "unknown comm mode %d", comm);
+    if (sched != ISO_SCHED_OVERLAP && sched != ISO_SCHED_SERIAL) return fail(ISO_ERR_SHAPE, "unknown schedule %d", sched);
+    return ISO_OK;
+}
+
+int run_stack(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, void *k_caches, void *v_caches, int T,
+              int split, int comm, int sched) {
+    const iso_cfg &c = ctx->cfg;
+    const size_t cache_bytes = (size_t)c.max_seq * c.n_kv_heads * c.head_dim * ctx->elt;
+    const bool two = split > 0 && split < T;
+    const bool overlap = two && sched == ISO_SCHED_OVERLAP && ctx->stream[1] != ctx->stream[0];
+    hipStream_t s0 = ctx->stream[0], s1 = overlap ? ctx->stream[1] : ctx->stream[0];
+    Chunk ch[2] = {{0, two ? split : T, s0}, {split, T - split, s1}};
+    const int nc = two ? 2 : 1;
+
+    if (overlap) {   // fork: stream1 starts after whatever produced x in stream0
+        HIP_TRY(hipEventRecord(ctx->ev_fork, s0));
+        HIP_TRY(hipStreamWaitEvent(s1, ctx->ev_fork, 0));
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        const iso_weights *w = &layers[l];
+        void *kc = (char *)k_caches + (size_t)l * cache_bytes;
+        void *vc = (char *)v_caches + (size_t)l * cache_bytes;
+        // A0 head, then the KV event, then A1 head: chunk 1's norm/QKV/RoPE do not depend on chunk 0.
+        for (int k = 0; k < nc; ++k) {
+            ISO_TRY(attn_block_head(ctx, w, x, kc, vc, ch[k], l > 0));
+            if (k == 0 && overlap) HIP_TRY(hipEventRecord(ctx->ev_kv0, s0));
+        }
+        for (int k = 0; k < nc; ++k) {
+            if (k == 1 && overlap) HIP_TRY(hipStreamWaitEvent(s1, ctx->ev_kv0, 0));
+            ISO_TRY(attn_block_tail(ctx, w, kc, vc, ch[k], comm));
+        }
+        for (int k = 0; k < nc; ++k) ISO_TRY(mlp_block(ctx, w, x, ch[k], comm));
+    }
+    for (int k = 0; k < nc; ++k) ISO_TRY(final_residual(ctx, x, ch[k]));
+    if (overlap) {   // join: later work in stream0 sees both chunks
+        HIP_TRY(hipEventRecord(ctx->ev_join, s1));
+        HIP_TRY(hipStreamWaitEvent(s0, ctx->ev_join, 0));
+    }
+    return ISO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *iso_last_error(void) { return g_err; }
+
+int iso_validate_cfg(const iso_cfg *cfg) { return check_cfg(cfg); }
+
+int iso_plan_chunks(const iso_cfg *cfg, int T, int split, iso_plan *out) {
+    ISO_TRY(check_cfg(cfg));
+    if (!out) return fail(ISO_ERR_NULL, "out is NULL");
+    if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
+    if (T > cfg->max_seq) return fail(ISO_ERR_WORKSPACE, "T=%d exceeds max_seq=%d", T, cfg->max_seq);
+    if (split < 0 || split > T) return fail(ISO_ERR_SPLIT, "split=%d outside [0, %d]", split, T);
+    memset(out, 0, sizeof(*out));
+    const bool two = split > 0 && split < T;
+    out->n_chunks = two ? 2 : 1;
+    out->q_offset[0] = 0;
+    out->n_tokens[0] = two ? split : T;
+    out->kv_len[0] = out->n_tokens[0];
+    if (two) {
+        out->q_offset[1] = split;
+        out->n_tokens[1] = T - split;
+        out->kv_len[1] = T;
+    }
+    for (int k = 0; k < out->n_chunks; ++k)
+        out->comm_bytes[k] = (size_t)out->n_tokens[k] * cfg->hidden * elt_size(cfg->dtype);
+    out->workspace_bytes = ws_layout(*cfg).total;
+    return ISO_OK;
+}
+
+int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) {
+    if (!out) return fail(ISO_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    ISO_TRY(check_cfg(cfg));
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    iso_ctx *ctx = new iso_ctx();
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->cfg = *cfg;
+    ctx->device = dev;
+    ctx->stream[0] = (hipStream_t)stream0;
+    ctx->stream[1] = (hipStream_t)stream1;
+    ctx->elt = elt_size(cfg->dtype);
+    ctx->tev0 = new hipEvent_t[ISO_MAX_TIMED]();
+    ctx->tev1 = new hipEvent_t[ISO_MAX_TIMED]();
+    ctx->tkind = new int[ISO_MAX_TIMED]();
+    const WsLayout l = ws_layout(*cfg);
+    const size_t half = (size_t)cfg->head_dim / 2;
+    const size_t table = (size_t)cfg->max_seq * half;
+    int rc = ISO_OK;
+    auto hip_ok = [&](hipError_t e, const char *what) {
+        if (e != hipSuccess && rc == ISO_OK) rc = fail(ISO_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+        return e == hipSuccess;
+    };
+    do {
+        if (!hip_ok(hipMalloc(&ctx->ws, l.total), "hipMalloc(workspace)")) break;
+        ctx->ws_bytes = l.total;
+        char *b = (char *)ctx->ws;
+        ctx->y = b + l.y; ctx->qkv = b + l.qkv; ctx->attn = b + l.attn;
+        ctx->part = b + l.part; ctx->gu = b + l.gu; ctx->act = b + l.act;
+        if (!hip_ok(hipMalloc((void **)&ctx->rope_cos, table * sizeof(float)), "hipMalloc(rope cos)")) break;
+        if (!hip_ok(hipMalloc((void **)&ctx->rope_sin, table * sizeof(float)), "hipMalloc(rope sin)")) break;
+        {   // rotary table: angles in double on the host, stored as fp32
+            std::vector<float> hc(table), hs(table);
+            for (size_t i = 0; i < half; ++i) {
+                const double inv_freq = pow((double)cfg->rope_base, -2.0 * (double)i / (double)cfg->head_dim);
+                for (size_t p = 0; p < (size_t)cfg->max_seq; ++p) {
+                    const double ang = (double)p * inv_freq;
+                    hc[p * half + i] = (float)cos(ang);
+                    hs[p * half + i] = (float)sin(ang);
+                }
+            }
+            if (!hip_ok(hipMemcpy(ctx->rope_cos, hc.data(), table * sizeof(float), hipMemcpyHostToDevice), "copy rope cos")) break;
+            if (!hip_ok(hipMemcpy(ctx->rope_sin, hs.data(), table * sizeof(float), hipMemcpyHostToDevice), "copy rope sin")) break;
+        }
+        if (!hip_ok(hipHostMalloc(&ctx->host_sink, 2 * (size_t)cfg->max_seq * cfg->hidden * ctx->elt, hipHostMallocDefault),
+                    "hipHostMalloc(sink)")) break;
+        if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming), "event")) break;
+        if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming), "event")) break;
+        if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_kv0, hipEventDisableTiming), "event")) break;
+    } while (0);
+    if (rc != ISO_OK) {
+        char keep[sizeof(g_err)];
+        memcpy(keep, g_err, sizeof(keep));
+        iso_destroy(ctx);
+        memcpy(g_err, keep, sizeof(keep));
+        return rc;
+    }
+    *out = ctx;
+    return ISO_OK;
+}
+
+int iso_sync(iso_ctx *ctx) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    HIP_TRY(hipStreamSynchronize(ctx->stream[0]));
+    if (ctx->stream[1] != ctx->stream[0]) HIP_TRY(hipStreamSynchronize(ctx->stream[1]));
+    return ISO_OK;
+}
+
+int iso_destroy(iso_ctx *ctx) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (ctx->ws) {   // only a fully or partly built context has device state to drain
+        (void)hipStreamSynchronize(ctx->stream[0]);
+        if (ctx->stream[1] != ctx->stream[0]) (void)hipStreamSynchronize(ctx->stream[1]);
+    }
+    for (int i = 0; i < ctx->n_tev_created; ++i) {
+        (void)hipEventDestroy(ctx->tev0[i]);
+        (void)hipEventDestroy(ctx->tev1[i]);
+    }
+    delete[] ctx->tev0;
+    delete[] ctx->tev1;
+    delete[] ctx->tkind;
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+    if (ctx->ev_kv0) (void)hipEventDestroy(ctx->ev_kv0);
+    if (ctx->host_sink) (void)hipHostFree(ctx->host_sink);
+    if (ctx->rope_cos) (void)hipFree(ctx->rope_cos);
+    if (ctx->rope_sin) (void)hipFree(ctx->rope_sin);
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    delete ctx;
+    return ISO_OK;
+}
+
+int iso_set_flags(iso_ctx *ctx, int flags) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    ctx->flags = flags;
+    return ISO_OK;
+}
+
+int iso_timing_enable(iso_ctx *ctx, int on) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    ctx->timing = on ? 1 : 0;
+    ctx->n_tev = 0;
+    return ISO_OK;
+}
+
+int iso_timing_read(iso_ctx *ctx, int kind, double *total_ms, int *launches) {
+    if (!ctx || !total_ms || !launches) return fail(ISO_ERR_NULL, "ctx, total_ms and launches must be non-NULL");
+    if (kind < 0 || kind >= ISO_K_COUNT) return fail(ISO_ERR_SHAPE, "unknown kernel kind %d", kind);
+    ISO_TRY(iso_sync(ctx));
+    double sum = 0.0;
+    int n = 0;
+    for (int i = 0; i < ctx->n_tev; ++i) {
+        if (ctx->tkind[i] != kind) continue;
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, ctx->tev0[i], ctx->tev1[i]));
+        sum += ms;
+        ++n;
+    }
+    *total_ms = sum;
+    *launches = n;
+    return ISO_OK;
+}
+
+void *iso_host_sink(iso_ctx *ctx) { return ctx ? ctx->host_sink : nullptr; }
+
+int iso_layer_prefill(iso_ctx *ctx, const iso_weights *w, void *x, void *k_cache, void *v_cache, int T, int split,
+                      int comm, int sched) {
+    ISO_TRY(check_layer_args(ctx, w, 1, x, k_cache, v_cache, T, split, comm, sched));
+    return run_stack(ctx, w, 1, x, k_cache, v_cache, T, split, comm, sched);
+}
+
+int iso_stack_prefill(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, void *k_caches, void *v_caches,
+                      int T, int split, int comm, int sched) {
+    ISO_TRY(check_layer_args(ctx, layers, n_layers, x, k_caches, v_caches, T, split, comm, sched));
+    return run_stack(ctx, layers, n_layers, x, k_caches, v_caches, T, split, comm, sched);
+}
+
+int iso_attn_chunk(iso_ctx *ctx, const void *q, const void *k_cache, const void *v_cache, void *out, int Tc,
+                   int q_offset, int kv_len, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!q || !k_cache || !v_cache || !out) return fail(ISO_ERR_NULL, "q, k_cache, v_cache and out must be non-NULL");
+    if (Tc < 1) return fail(ISO_ERR_SHAPE, "Tc=%d must be positive", Tc);
+    if (q_offset < 0) return fail(ISO_ERR_SHAPE, "q_offset=%d must be >= 0", q_offset);
+    if (kv_len < 1) return fail(ISO_ERR_SHAPE, "kv_len=%d must be positive", kv_len);
+    if (kv_len > ctx->cfg.max_seq) return fail(ISO_ERR_WORKSPACE, "kv_len=%d exceeds max_seq=%d", kv_len, ctx->cfg.max_seq);
+    if (Tc > ctx->cfg.max_seq) return fail(ISO_ERR_WORKSPACE, "Tc=%d exceeds max_seq=%d", Tc, ctx->cfg.max_seq);
+    return attention(ctx, q, ctx->cfg.n_q_heads * ctx->cfg.head_dim, k_cache, v_cache, out, Tc, q_offset, kv_len,
+                     (hipStream_t)stream);
+}
+
+int iso_gemm_rowpar(iso_ctx *ctx, const void *a, const void *w, void *c, int M, int N, int K, void *stream,
+                    void *host_sink) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!a || !w || !c) return fail(ISO_ERR_NULL, "a, w and c must be non-NULL");
+    if (M < 1 || N < 1 || K < 1) return fail(ISO_ERR_SHAPE, "M=%d N=%d K=%d must be positive", M, N, K);
+    if (ctx->cfg.dtype == ISO_BF16 && (K % 8)) return fail(ISO_ERR_SHAPE, "K=%d must be a multiple of 8 for bf16", K);
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_O, a, w, c, M, N, K, (hipStream_t)stream));
+    if (host_sink) {
+        Timed t_(ctx, ISO_K_COMM, (hipStream_t)stream);
+        HIP_TRY(hipMemcpyAsync(host_sink, c, (size_t)M * N * ctx->elt, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    }
+    return ISO_OK;
+}
+
+int iso_rmsnorm(iso_ctx *ctx, const void *x, const void *g, void *y, int T, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!x || !g || !y) return fail(ISO_ERR_NULL, "x, g and y must be non-NULL");
+    if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
+    LAUNCH_TRY(ISO_K_RMSNORM, (hipStream_t)stream, iso_launch_rmsnorm(ctx->cfg.dtype, x, nullptr, nullptr, g, y, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
+                                  (hipStream_t)stream), "rmsnorm");
+    return ISO_OK;
+}
+
+int iso_residual_rmsnorm(iso_ctx *ctx, void *x, const void *delta, const void *g, void *y, int T, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!x || !delta) return fail(ISO_ERR_NULL, "x and delta must be non-NULL");
+    if ((y != nullptr) != (g != nullptr)) return fail(ISO_ERR_NULL, "g and y must both be given or both be NULL");
+    if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
+    LAUNCH_TRY(y ? ISO_K_RESID_NORM : ISO_K_RESIDUAL, (hipStream_t)stream, iso_launch_rmsnorm(ctx->cfg.dtype, x, delta, x, g, y, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
+                                  (hipStream_t)stream), "residual+rmsnorm");
+    return ISO_OK;
+}
+
+int iso_rope_kv_write(iso_ctx *ctx, void *qkv, void *k_cache, void *v_cache, int Tc, int q_offset, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!qkv || !k_cache || !v_cache) return fail(ISO_ERR_NULL, "qkv, k_cache and v_cache must be non-NULL");
+    if (Tc < 1 || q_offset < 0) return fail(ISO_ERR_SHAPE, "Tc=%d must be positive and q_offset=%d >= 0", Tc, q_offset);
+    if ((long long)q_offset + Tc > ctx->cfg.max_seq)
+        return fail(ISO_ERR_WORKSPACE, "q_offset+Tc=%lld exceeds max_seq=%d", (long long)q_offset + Tc, ctx->cfg.max_seq);
+    const iso_cfg &c = ctx->cfg;
+    LAUNCH_TRY(ISO_K_ROPE_KV, (hipStream_t)stream, iso_launch_rope_kv(c.dtype, qkv, k_cache, v_cache, ctx->rope_cos, ctx->rope_sin, Tc, q_offset,
+                                  c.n_q_heads, c.n_kv_heads, c.head_dim, (hipStream_t)stream), "rope+kv");
+    return ISO_OK;
+}
+
+int iso_swiglu(iso_ctx *ctx, const void *gu, void *a, int T, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!gu || !a) return fail(ISO_ERR_NULL, "gu and a must be non-NULL");
+    if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
+    LAUNCH_TRY(ISO_K_SWIGLU, (hipStream_t)stream, iso_launch_swiglu(ctx->cfg.dtype, gu, a, T, ctx->cfg.ffn, (hipStream_t)stream), "swiglu");
+    return ISO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Internal declarations shared by the HIP sources of libiso (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "iso.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+struct iso_ctx {
+    iso_cfg cfg;
+    int device;
+    int flags;
+    hipStream_t stream[2];
+    hipEvent_t ev_fork, ev_join, ev_kv0;
+    size_t elt;        // bytes per element
+    // device workspace, each sized for max_seq tokens; chunks use disjoint row ranges
+    void *ws;          // one allocation
+    size_t ws_bytes;
+    void *y;           // [max_seq, hidden]   normed activations (both norms)
+    void *qkv;         // [max_seq, n_qkv]
+    void *attn;        // [max_seq, nq*d]
+    void *part;        // [max_seq, hidden]   row-parallel partial (o_proj, then down)
+    void *gu;          // [max_seq, 2*ffn]
+    void *act;         // [max_seq, ffn]
+    float *rope_cos;   // [max_seq, d/2]
+    float *rope_sin;   // [max_seq, d/2]
+    void *host_sink;   // pinned, 2 * max_seq * hidden elements
+    // optional per-launch timing (iso_timing_*): event pairs recorded around every launch, in its stream
+    int timing;
+    int n_tev, n_tev_created;
+    hipEvent_t *tev0, *tev1;
+    int *tkind;
+};
+constexpr int ISO_MAX_TIMED = 8192;
+
+// ---- launchers; each validates nothing (callers do) and returns the launch status -------------
+hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta_or_null, void *x_out_or_null,
+                              const void *g, void *y_or_null, int T, int H, float eps, hipStream_t s);
+hipError_t iso_launch_rope_kv(int dtype, void *qkv, void *k_cache, void *v_cache, const float *cos_t,
+                              const float *sin_t, int Tc, int q_offset, int nq, int nkv, int d, hipStream_t s);
+hipError_t iso_launch_swiglu(int dtype, const void *gu, void *a, int T, int F, hipStream_t s);
+hipError_t iso_launch_gemm_simple(int dtype, const void *a, const void *w, void *c, int M, int N, int K,
+                                  hipStream_t s);
+hipError_t iso_launch_gemm_bf16_mfma(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s);
+bool iso_gemm_bf16_mfma_supported(int M, int N, int K);
+hipError_t iso_launch_attn_simple(int dtype, const void *q, const void *k, const void *v, void *out, int Tc,
+                                  int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
+hipError_t iso_launch_attn_bf16_mfma(const void *q, const void *k, const void *v, void *out, int Tc,
+                                     int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
+bool iso_attn_bf16_mfma_supported(int d);
+
+// ---- small device helpers ----------------------------------------------------------------------
+__device__ __forceinline__ float iso_to_f32(float v) { return v; }
+__device__ __forceinline__ float iso_to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T iso_from_f32(float v);
+template <> __device__ __forceinline__ float iso_from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t iso_from_f32<bf16_t>(float v) { return (bf16_t)v; }  // RNE
+
+__device__ __forceinline__ float iso_wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float iso_wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}

@@ -1,0 +1,96 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the header
+declares, validates configurations and plans chunks, and refuses bad arguments with error codes."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2409_11155_amd as iso
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _good_cfg(**over):
+    kw = dict(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=688, dtype=iso.ISO_F32, max_seq=128)
+    kw.update(over)
+    return iso.make_cfg(**kw)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = iso.load()
+    with open(os.path.join(ROOT, "include", "iso.h")) as f:
+        header = f.read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(iso_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations parsed"
+    assert declared == set(iso.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_validate_cfg_accepts_the_workloads_and_rejects_bad_fields():
+    import iso_inputs
+    for wl in iso_inputs.WORKLOADS.values():
+        cfg = iso.make_cfg(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.dtype, wl.seq)
+        assert iso.validate_cfg(cfg) == iso.ISO_OK, wl.name
+    assert iso.validate_cfg(_good_cfg(hidden=250)) == iso.ISO_ERR_SHAPE
+    assert iso.validate_cfg(_good_cfg(ffn=0)) == iso.ISO_ERR_SHAPE
+    assert iso.validate_cfg(_good_cfg(head_dim=96)) == iso.ISO_ERR_SHAPE
+    assert iso.validate_cfg(_good_cfg(n_q_heads=6, n_kv_heads=4)) == iso.ISO_ERR_SHAPE
+    assert iso.validate_cfg(_good_cfg(n_kv_heads=0)) == iso.ISO_ERR_SHAPE
+    assert iso.validate_cfg(_good_cfg(max_seq=0)) == iso.ISO_ERR_SHAPE
+    assert iso.validate_cfg(_good_cfg(dtype=7)) == iso.ISO_ERR_DTYPE
+    assert iso.validate_cfg(_good_cfg(rope_base=1.0)) == iso.ISO_ERR_SHAPE
+    assert iso.load().iso_validate_cfg(None) == iso.ISO_ERR_NULL
+    assert "NULL" in iso.last_error()
+
+
+def test_plan_chunks():
+    cfg = _good_cfg(max_seq=8192, hidden=8192, dtype=iso.ISO_BF16, head_dim=128, n_q_heads=16, n_kv_heads=2, ffn=7168)
+    p = iso.plan_chunks(cfg, 8192, 4928)
+    assert p.n_chunks == 2
+    assert list(p.q_offset) == [0, 4928] and list(p.n_tokens) == [4928, 3264] and list(p.kv_len) == [4928, 8192]
+    assert list(p.comm_bytes) == [4928 * 8192 * 2, 3264 * 8192 * 2]
+    assert p.workspace_bytes >= 8192 * (2 * 8192 + 2560 + 2048 + 3 * 7168) * 2
+    for s in (0, 8192):
+        p = iso.plan_chunks(cfg, 8192, s)
+        assert p.n_chunks == 1 and p.n_tokens[0] == 8192 and p.kv_len[0] == 8192
+    p = iso.plan_chunks(cfg, 100, 1)
+    assert list(p.n_tokens) == [1, 99]
+    for T, s, code in ((8193, 10, iso.ISO_ERR_WORKSPACE), (100, -1, iso.ISO_ERR_SPLIT), (100, 101, iso.ISO_ERR_SPLIT),
+                       (0, 0, iso.ISO_ERR_SHAPE)):
+        with pytest.raises(iso.IsoError) as ei:
+            iso.plan_chunks(cfg, T, s)
+        assert ei.value.code == code
+
+
+def test_null_context_and_null_out_are_refused_without_touching_a_device():
+    lib = iso.load()
+    w = iso.IsoWeights()
+    assert lib.iso_layer_prefill(None, ctypes.byref(w), None, None, None, 4, 2, 0, 0) == iso.ISO_ERR_NULL
+    assert lib.iso_stack_prefill(None, ctypes.byref(w), 1, None, None, None, 4, 2, 0, 0) == iso.ISO_ERR_NULL
+    assert lib.iso_attn_chunk(None, None, None, None, None, 1, 0, 1, None) == iso.ISO_ERR_NULL
+    assert lib.iso_gemm_rowpar(None, None, None, None, 1, 1, 8, None, None) == iso.ISO_ERR_NULL
+    assert lib.iso_rmsnorm(None, None, None, None, 1, None) == iso.ISO_ERR_NULL
+    assert lib.iso_residual_rmsnorm(None, None, None, None, None, 1, None) == iso.ISO_ERR_NULL
+    assert lib.iso_rope_kv_write(None, None, None, None, 1, 0, None) == iso.ISO_ERR_NULL
+    assert lib.iso_swiglu(None, None, None, 1, None) == iso.ISO_ERR_NULL
+    assert lib.iso_sync(None) == iso.ISO_ERR_NULL
+    assert lib.iso_destroy(None) == iso.ISO_ERR_NULL
+    assert lib.iso_set_flags(None, 0) == iso.ISO_ERR_NULL
+    assert lib.iso_host_sink(None) is None
+    cfg = _good_cfg()
+    assert lib.iso_create(None, ctypes.byref(cfg), None, None) == iso.ISO_ERR_NULL
+    handle = ctypes.c_void_p(1234)
+    bad = _good_cfg(head_dim=80)
+    assert lib.iso_create(ctypes.byref(handle), ctypes.byref(bad), None, None) == iso.ISO_ERR_SHAPE
+    assert handle.value is None          # *out is cleared on failure
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="checks the no-device error path")
+def test_create_without_a_device_reports_a_hip_error():
+    with pytest.raises(iso.IsoError) as ei:
+        iso.Context(_good_cfg())
+    assert ei.value.code == iso.ISO_ERR_HIP
