@@ -164,8 +164,10 @@ int iso_swiglu(iso_ctx *ctx, const void *gu, void *a, int T, void *stream);
 /* Kernel selection, for tests and measurement.  Default 0 = the matrix-core kernels wherever the dtype
  * and shapes allow.  The forced alternatives are complete HIP kernels as well (they are the fp32 path). */
 enum {
-    ISO_FLAG_SIMPLE_GEMM = 1, /* SIMT tile GEMM instead of the MFMA GEMM                  */
-    ISO_FLAG_SIMPLE_ATTN = 2  /* one-wave-per-row attention instead of the MFMA attention */
+    ISO_FLAG_SIMPLE_GEMM = 1, /* SIMT tile GEMM instead of the MFMA GEMMs                  */
+    ISO_FLAG_SIMPLE_ATTN = 2, /* one-wave-per-row attention instead of the MFMA attention  */
+    ISO_FLAG_GEMM_STAGED = 4  /* register-staged 128x128 MFMA GEMM instead of the direct-to-LDS one */
+    /* bits 8..11: tile variant of the direct-to-LDS GEMM (0 = chosen from the shape) */
 };
 int iso_set_flags(iso_ctx *ctx, int flags);
 

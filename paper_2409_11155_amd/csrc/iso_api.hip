@@ -99,7 +99,10 @@ inline const char *at(const void *base, size_t row, size_t width, size_t e) { re
 int gemm(iso_ctx *ctx, int kind, const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     Timed t_(ctx, kind, s);
     hipError_t e;
-    if (ctx->cfg.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_GEMM) && iso_gemm_bf16_mfma_supported(M, N, K))
+    const bool mfma = ctx->cfg.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_GEMM);
+    if (mfma && !(ctx->flags & ISO_FLAG_GEMM_STAGED) && iso_gemm_bf16_dtl_supported(M, N, K))
+        e = iso_launch_gemm_bf16_dtl(a, w, c, M, N, K, (ctx->flags >> 8) & 15, s);
+    else if (mfma && iso_gemm_bf16_mfma_supported(M, N, K))
         e = iso_launch_gemm_bf16_mfma(a, w, c, M, N, K, s);
     else
         e = iso_launch_gemm_simple(ctx->cfg.dtype, a, w, c, M, N, K, s);

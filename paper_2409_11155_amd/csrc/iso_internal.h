@@ -50,6 +50,9 @@ hipError_t iso_launch_gemm_simple(int dtype, const void *a, const void *w, void 
                                   hipStream_t s);
 hipError_t iso_launch_gemm_bf16_mfma(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s);
 bool iso_gemm_bf16_mfma_supported(int M, int N, int K);
+hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M, int N, int K, int variant,
+                                    hipStream_t s);
+bool iso_gemm_bf16_dtl_supported(int M, int N, int K);
 hipError_t iso_launch_attn_simple(int dtype, const void *q, const void *k, const void *v, void *out, int Tc,
                                   int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
 hipError_t iso_launch_attn_bf16_mfma(const void *q, const void *k, const void *v, void *out, int Tc,
