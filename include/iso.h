@@ -166,7 +166,8 @@ int iso_swiglu(iso_ctx *ctx, const void *gu, void *a, int T, void *stream);
 enum {
     ISO_FLAG_SIMPLE_GEMM = 1, /* SIMT tile GEMM instead of the MFMA GEMMs                  */
     ISO_FLAG_SIMPLE_ATTN = 2, /* one-wave-per-row attention instead of the MFMA attention  */
-    ISO_FLAG_GEMM_STAGED = 4  /* register-staged 128x128 MFMA GEMM instead of the direct-to-LDS one */
+    ISO_FLAG_GEMM_STAGED = 4, /* register-staged 128x128 MFMA GEMM instead of the direct-to-LDS one */
+    ISO_FLAG_NO_FUSE = 8      /* gate/up projection and SwiGLU as two kernels instead of one        */
     /* bits 8..11: tile variant of the direct-to-LDS GEMM (0 = chosen from the shape) */
 };
 int iso_set_flags(iso_ctx *ctx, int flags);
@@ -182,6 +183,22 @@ typedef enum {
 } iso_kernel_kind;
 int iso_timing_enable(iso_ctx *ctx, int on);
 int iso_timing_read(iso_ctx *ctx, int kind, double *total_ms, int *launches);
+
+/* Device plumbing, so that callers need nothing but this library to hold buffers and streams.  All of
+ * these act on the current HIP device of the calling thread; copies are synchronous (they return when
+ * the bytes have arrived).  Errors: ISO_ERR_NULL, ISO_ERR_HIP. */
+int iso_device_count(int *count);                         /* 0 devices is ISO_OK with *count == 0  */
+int iso_device_sync(void);                                /* hipDeviceSynchronize                   */
+int iso_dev_alloc(void **ptr, size_t bytes);              /* device memory, 256-byte aligned        */
+int iso_dev_free(void *ptr);
+int iso_dev_fill(void *ptr, int byte_value, size_t bytes);
+int iso_host_alloc(void **ptr, size_t bytes);             /* pinned host memory                     */
+int iso_host_free(void *ptr);
+int iso_copy_h2d(void *dst_dev, const void *src_host, size_t bytes);
+int iso_copy_d2h(void *dst_host, const void *src_dev, size_t bytes);
+int iso_copy_d2d(void *dst_dev, const void *src_dev, size_t bytes);
+int iso_stream_create(void **stream);                     /* non-blocking stream, default priority  */
+int iso_stream_destroy(void *stream);
 
 /* Pinned host buffer the context uses for ISO_COMM_D2H (2 * max_seq * hidden elements), for tests. */
 void *iso_host_sink(iso_ctx *ctx);

@@ -17,7 +17,38 @@ from __future__ import annotations
 import dataclasses
 from typing import Dict
 
-import torch
+import numpy as np
+
+
+# ---- bf16 storage format: the upper 16 bits of an IEEE float32, rounded to nearest even ------------
+# (format conversion for input preparation; arrays of bf16 values are held as uint16 bit patterns)
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def store(a: np.ndarray, dtype: str) -> np.ndarray:
+    """fp32 draw -> storage array of the workload dtype ("f32": float32, "bf16": uint16 bit patterns)."""
+    if dtype == "f32":
+        return np.ascontiguousarray(a, dtype=np.float32)
+    return f32_to_bf16_bits(a)
+
+
+def to_f64(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact float64 values of a storage array (what both the oracle and the GPU see)."""
+    if dtype == "f32":
+        return np.asarray(a, dtype=np.float32).astype(np.float64)
+    return bf16_bits_to_f32(a).astype(np.float64)
+
+
+def np_storage_dtype(dtype: str):
+    return np.float32 if dtype == "f32" else np.uint16
 
 
 @dataclasses.dataclass(frozen=True)
@@ -38,10 +69,6 @@ class Workload:
     @property
     def n_qkv(self) -> int:
         return (self.n_q_heads + 2 * self.n_kv_heads) * self.head_dim
-
-    @property
-    def torch_dtype(self) -> torch.dtype:
-        return torch.float32 if self.dtype == "f32" else torch.bfloat16
 
     def gemm_flops(self, tokens: int | None = None) -> float:
         """2*M*N*K over the four projections of one layer."""
@@ -82,56 +109,58 @@ WORKLOADS: Dict[str, Workload] = {
 }
 
 
-def _randn(gen: torch.Generator, *shape: int) -> torch.Tensor:
-    return torch.randn(*shape, generator=gen, dtype=torch.float32)
+def _randn(gen: np.random.Generator, *shape: int) -> np.ndarray:
+    return gen.standard_normal(shape, dtype=np.float32)
 
 
 def make_layer(hidden: int, n_q_heads: int, n_kv_heads: int, head_dim: int, ffn: int,
-               seed: int, dtype: torch.dtype) -> Dict[str, torch.Tensor]:
-    """Random weights of one layer shard (CPU tensors, already cast to `dtype`).
+               seed: int, dtype: str) -> Dict[str, np.ndarray]:
+    """Random weights of one layer shard, as storage arrays of `dtype` ("f32" or "bf16").
 
-    Draw order: w_qkv, w_o, w_gate_up, w_down, g_attn, g_mlp (fp32 draws, then a
-    round-to-nearest-even cast for bf16).
+    Draw order: w_qkv, w_o, w_gate_up, w_down, g_attn, g_mlp (fp32 draws from numpy's PCG64 seeded with
+    `seed`, then a round-to-nearest-even cast for bf16).
     """
-    gen = torch.Generator(device="cpu")
-    gen.manual_seed(seed)
+    gen = np.random.default_rng(seed)
     n_qkv = (n_q_heads + 2 * n_kv_heads) * head_dim
     nqd = n_q_heads * head_dim
     w = {
-        "w_qkv": _randn(gen, n_qkv, hidden) * hidden ** -0.5,
-        "w_o": _randn(gen, hidden, nqd) * nqd ** -0.5,
-        "w_gate_up": _randn(gen, 2 * ffn, hidden) * hidden ** -0.5,
-        "w_down": _randn(gen, hidden, ffn) * ffn ** -0.5,
-        "g_attn": 1.0 + 0.1 * _randn(gen, hidden),
-        "g_mlp": 1.0 + 0.1 * _randn(gen, hidden),
+        "w_qkv": _randn(gen, n_qkv, hidden) * np.float32(hidden ** -0.5),
+        "w_o": _randn(gen, hidden, nqd) * np.float32(nqd ** -0.5),
+        "w_gate_up": _randn(gen, 2 * ffn, hidden) * np.float32(hidden ** -0.5),
+        "w_down": _randn(gen, hidden, ffn) * np.float32(ffn ** -0.5),
+        "g_attn": np.float32(1.0) + np.float32(0.1) * _randn(gen, hidden),
+        "g_mlp": np.float32(1.0) + np.float32(0.1) * _randn(gen, hidden),
     }
-    return {k: v.to(dtype).contiguous() for k, v in w.items()}
+    return {k: store(v, dtype) for k, v in w.items()}
 
 
-def make_hidden(seq: int, hidden: int, seed: int, dtype: torch.dtype) -> torch.Tensor:
+def make_hidden(seq: int, hidden: int, seed: int, dtype: str) -> np.ndarray:
     """Input hidden states x[seq, hidden] ~ N(0,1)."""
-    gen = torch.Generator(device="cpu")
-    gen.manual_seed(seed + 7919)
-    return _randn(gen, seq, hidden).to(dtype).contiguous()
+    gen = np.random.default_rng(seed + 7919)
+    return store(_randn(gen, seq, hidden), dtype)
 
 
 def make_workload_inputs(w: Workload, seed: int = 0, layer: int = 0):
     """(x, weights) for one layer of a named workload; layer l uses seed 1000*seed + l."""
-    weights = make_layer(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn,
-                         1000 * seed + layer, w.torch_dtype)
-    x = make_hidden(w.seq, w.hidden, seed, w.torch_dtype)
+    weights = make_layer(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, 1000 * seed + layer, w.dtype)
+    x = make_hidden(w.seq, w.hidden, seed, w.dtype)
     return x, weights
 
 
 def make_qkv_cache(tc: int, kv_len: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
-                   seed: int, dtype: torch.dtype):
+                   seed: int, dtype: str):
     """Random q[tc, nq, d], k[kv_len, nkv, d], v[kv_len, nkv, d] for attention-only tests."""
-    gen = torch.Generator(device="cpu")
-    gen.manual_seed(seed)
-    q = _randn(gen, tc, n_q_heads, head_dim).to(dtype)
-    k = _randn(gen, kv_len, n_kv_heads, head_dim).to(dtype)
-    v = _randn(gen, kv_len, n_kv_heads, head_dim).to(dtype)
-    return q.contiguous(), k.contiguous(), v.contiguous()
+    gen = np.random.default_rng(seed)
+    q = store(_randn(gen, tc, n_q_heads, head_dim), dtype)
+    k = store(_randn(gen, kv_len, n_kv_heads, head_dim), dtype)
+    v = store(_randn(gen, kv_len, n_kv_heads, head_dim), dtype)
+    return q, k, v
+
+
+def randn(shape, seed: int, dtype: str, scale: float = 1.0) -> np.ndarray:
+    """A seeded N(0, scale^2) storage array for single-step tests."""
+    gen = np.random.default_rng(seed)
+    return store(_randn(gen, *shape) * np.float32(scale), dtype)
 
 
 def sample_rows(seq: int, split: int, n: int, seed: int = 0):
@@ -139,13 +168,12 @@ def sample_rows(seq: int, split: int, n: int, seed: int = 0):
     fixed = {0, 1, seq - 1}
     if 0 < split < seq:
         fixed |= {split - 1, split, min(split + 1, seq - 1)}
-    gen = torch.Generator(device="cpu")
-    gen.manual_seed(seed + 104729)
+    gen = np.random.default_rng(seed + 104729)
     rows = set(r for r in fixed if 0 <= r < seq)
     s = split if 0 < split < seq else seq // 2
     while len(rows) < min(n, seq):
         lo, hi = (0, s) if len(rows) % 2 == 0 else (s, seq)
         if hi <= lo:
             lo, hi = 0, seq
-        rows.add(int(torch.randint(lo, hi, (1,), generator=gen)))
+        rows.add(int(gen.integers(lo, hi)))
     return sorted(rows)

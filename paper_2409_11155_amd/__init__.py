@@ -1,9 +1,15 @@
 """Python binding of libiso: argument marshalling only.
 
 Every step of the ISO layer-shard prefill runs inside the HIP kernels of libiso.so; this module turns
-torch tensors and streams into the plain pointers and sizes of the C ABI (include/iso.h) and turns error
-codes into exceptions.  There is no fallback: if the library is missing, importing a binding function
-raises.
+numpy arrays, device buffers and streams into the plain pointers and sizes of the C ABI (include/iso.h)
+and turns error codes into exceptions.  There is no fallback: if the library cannot be loaded, every
+call raises.
+
+Device buffers and streams come from the library itself (DeviceArray, Stream), so a process needs no
+other GPU framework.  Objects from other frameworks still work where a pointer is expected: anything with
+a `data_ptr()` method is taken as a device buffer and anything with a `cuda_stream` attribute as a stream.
+Import this package before any other library that bundles its own HIP runtime: the first HIP runtime
+loaded into the process is the one libiso binds to.
 """
 from __future__ import annotations
 
@@ -11,7 +17,7 @@ import ctypes
 import os
 from typing import Dict, Optional, Sequence
 
-import torch
+import numpy as np
 
 from . import build as _build
 
@@ -20,16 +26,20 @@ ISO_ERR_NULL, ISO_ERR_SHAPE, ISO_ERR_DTYPE, ISO_ERR_SPLIT, ISO_ERR_WORKSPACE, IS
 ISO_F32, ISO_BF16 = 0, 1
 ISO_COMM_NONE, ISO_COMM_D2H = 0, 1
 ISO_SCHED_OVERLAP, ISO_SCHED_SERIAL = 0, 1
-ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN, ISO_FLAG_GEMM_STAGED = 1, 2, 4
+ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN, ISO_FLAG_GEMM_STAGED, ISO_FLAG_NO_FUSE = 1, 2, 4, 8
 
 EXPORTS = [
     "iso_validate_cfg", "iso_plan_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",
     "iso_layer_prefill", "iso_stack_prefill", "iso_attn_chunk", "iso_gemm_rowpar", "iso_rmsnorm",
     "iso_residual_rmsnorm", "iso_rope_kv_write", "iso_swiglu", "iso_set_flags", "iso_host_sink",
     "iso_timing_enable", "iso_timing_read",
+    "iso_device_count", "iso_device_sync", "iso_dev_alloc", "iso_dev_free", "iso_dev_fill", "iso_host_alloc",
+    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
 ]
 KERNEL_KINDS = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn", "rmsnorm", "resid_norm", "residual",
                 "rope_kv", "swiglu", "comm"]
+DTYPE_BYTES = {"f32": 4, "bf16": 2}
+_NP_STORAGE = {"f32": np.float32, "bf16": np.uint16}
 
 
 class IsoCfg(ctypes.Structure):
@@ -70,12 +80,13 @@ def load() -> ctypes.CDLL:
     if not os.path.exists(_build.LIB_PATH):
         _build.build(verbose=False)
     lib = ctypes.CDLL(_build.LIB_PATH)
-    vp, ci = ctypes.c_void_p, ctypes.c_int
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    pvp = ctypes.POINTER(vp)
     lib.iso_last_error.restype = ctypes.c_char_p
     lib.iso_last_error.argtypes = []
     lib.iso_validate_cfg.argtypes = [ctypes.POINTER(IsoCfg)]
     lib.iso_plan_chunks.argtypes = [ctypes.POINTER(IsoCfg), ci, ci, ctypes.POINTER(IsoPlan)]
-    lib.iso_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(IsoCfg), vp, vp]
+    lib.iso_create.argtypes = [pvp, ctypes.POINTER(IsoCfg), vp, vp]
     lib.iso_destroy.argtypes = [vp]
     lib.iso_sync.argtypes = [vp]
     lib.iso_set_flags.argtypes = [vp, ci]
@@ -91,6 +102,18 @@ def load() -> ctypes.CDLL:
     lib.iso_swiglu.argtypes = [vp, vp, vp, ci, vp]
     lib.iso_timing_enable.argtypes = [vp, ci]
     lib.iso_timing_read.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
+    lib.iso_device_count.argtypes = [ctypes.POINTER(ci)]
+    lib.iso_device_sync.argtypes = []
+    lib.iso_dev_alloc.argtypes = [pvp, sz]
+    lib.iso_dev_free.argtypes = [vp]
+    lib.iso_dev_fill.argtypes = [vp, ci, sz]
+    lib.iso_host_alloc.argtypes = [pvp, sz]
+    lib.iso_host_free.argtypes = [vp]
+    lib.iso_copy_h2d.argtypes = [vp, vp, sz]
+    lib.iso_copy_d2h.argtypes = [vp, vp, sz]
+    lib.iso_copy_d2d.argtypes = [vp, vp, sz]
+    lib.iso_stream_create.argtypes = [pvp]
+    lib.iso_stream_destroy.argtypes = [vp]
     for name in EXPORTS:
         if name not in ("iso_last_error", "iso_host_sink"):
             getattr(lib, name).restype = ci
@@ -107,11 +130,19 @@ def _check(code: int) -> None:
         raise IsoError(code, last_error())
 
 
+def device_count() -> int:
+    n = ctypes.c_int(0)
+    _check(load().iso_device_count(ctypes.byref(n)))
+    return n.value
+
+
+def device_sync() -> None:
+    _check(load().iso_device_sync())
+
+
 def make_cfg(hidden: int, n_q_heads: int, n_kv_heads: int, head_dim: int, ffn: int, dtype, max_seq: int,
              rms_eps: float = 1e-6, rope_base: float = 10000.0) -> IsoCfg:
-    if isinstance(dtype, torch.dtype):
-        dtype = {torch.float32: ISO_F32, torch.bfloat16: ISO_BF16}[dtype]
-    elif isinstance(dtype, str):
+    if isinstance(dtype, str):
         dtype = {"f32": ISO_F32, "bf16": ISO_BF16}[dtype]
     return IsoCfg(hidden, n_q_heads, n_kv_heads, head_dim, ffn, rms_eps, rope_base, int(dtype), max_seq)
 
@@ -126,34 +157,159 @@ def plan_chunks(cfg: IsoCfg, T: int, split: int) -> IsoPlan:
     return plan
 
 
-def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+# ------------------------------------------------------------------------------ buffers and streams
+
+class DeviceArray:
+    """A device allocation with a shape and an element type ("f32" or "bf16").  bf16 values travel to and
+    from the host as uint16 bit patterns (numpy has no bf16)."""
+
+    def __init__(self, shape, dtype: str, fill_byte: Optional[int] = None):
+        self._lib = load()
+        self.shape = tuple(int(s) for s in (shape if isinstance(shape, (tuple, list)) else (shape,)))
+        self.dtype = dtype
+        self.nbytes = int(np.prod(self.shape, dtype=np.int64)) * DTYPE_BYTES[dtype]
+        p = ctypes.c_void_p()
+        _check(self._lib.iso_dev_alloc(ctypes.byref(p), self.nbytes))
+        self.ptr = p.value
+        if fill_byte is not None:
+            self.fill(fill_byte)
+
+    @classmethod
+    def from_numpy(cls, a: np.ndarray, dtype: str) -> "DeviceArray":
+        a = np.ascontiguousarray(a)
+        if a.dtype != _NP_STORAGE[dtype]:
+            raise TypeError(f"{dtype} arrays are stored as {_NP_STORAGE[dtype].__name__}, got {a.dtype}")
+        out = cls(a.shape, dtype)
+        out.upload(a)
+        return out
+
+    def upload(self, a: np.ndarray) -> None:
+        a = np.ascontiguousarray(a)
+        if a.nbytes != self.nbytes:
+            raise ValueError("size mismatch")
+        _check(self._lib.iso_copy_h2d(self.ptr, a.ctypes.data, self.nbytes))
+
+    def numpy(self) -> np.ndarray:
+        out = np.empty(self.shape, dtype=_NP_STORAGE[self.dtype])
+        _check(self._lib.iso_copy_d2h(out.ctypes.data, self.ptr, self.nbytes))
+        return out
+
+    def fill(self, byte_value: int) -> None:
+        _check(self._lib.iso_dev_fill(self.ptr, byte_value, self.nbytes))
+
+    def copy_from(self, other: "DeviceArray") -> None:
+        if other.nbytes != self.nbytes:
+            raise ValueError("size mismatch")
+        _check(self._lib.iso_copy_d2d(self.ptr, other.ptr, self.nbytes))
+
+    def clone(self) -> "DeviceArray":
+        out = DeviceArray(self.shape, self.dtype)
+        out.copy_from(self)
+        return out
+
+    def data_ptr(self) -> int:
+        return self.ptr
+
+    def free(self) -> None:
+        if getattr(self, "ptr", None):
+            self._lib.iso_dev_free(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class PinnedArray:
+    """Pinned host memory viewed as a numpy array (for the communication stand-in's destination)."""
+
+    def __init__(self, shape, dtype: str):
+        self._lib = load()
+        self.shape = tuple(shape)
+        self.dtype = dtype
+        self.nbytes = int(np.prod(self.shape, dtype=np.int64)) * DTYPE_BYTES[dtype]
+        p = ctypes.c_void_p()
+        _check(self._lib.iso_host_alloc(ctypes.byref(p), self.nbytes))
+        self.ptr = p.value
+        buf = (ctypes.c_byte * self.nbytes).from_address(self.ptr)
+        self.array = np.frombuffer(buf, dtype=_NP_STORAGE[dtype]).reshape(self.shape)
+
+    def free(self) -> None:
+        if getattr(self, "ptr", None):
+            self.array = None
+            self._lib.iso_host_free(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class Stream:
+    """A non-blocking HIP stream of default priority."""
+
+    def __init__(self):
+        self._lib = load()
+        p = ctypes.c_void_p()
+        _check(self._lib.iso_stream_create(ctypes.byref(p)))
+        self.handle = p.value
+
+    def destroy(self) -> None:
+        if getattr(self, "handle", None):
+            self._lib.iso_stream_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _ptr(t) -> Optional[int]:
     if t is None:
         return None
-    if not t.is_contiguous():
-        raise ValueError("libiso takes contiguous tensors")
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "is_contiguous") and not t.is_contiguous():
+        raise ValueError("libiso takes contiguous buffers")
     return t.data_ptr()
 
 
 def _stream_handle(s) -> Optional[int]:
     if s is None:
         return None
-    if isinstance(s, torch.cuda.Stream):
+    if isinstance(s, Stream):
+        return s.handle
+    if hasattr(s, "cuda_stream"):
         return s.cuda_stream or None
     return int(s) or None
 
 
-def pack_weights(w: Dict[str, torch.Tensor]) -> IsoWeights:
+def pack_weights(w: Dict[str, object]) -> IsoWeights:
     return IsoWeights(_ptr(w["w_qkv"]), _ptr(w["w_o"]), _ptr(w["w_gate_up"]), _ptr(w["w_down"]),
                       _ptr(w["g_attn"]), _ptr(w["g_mlp"]))
 
 
-class Context:
-    """Owns an iso_ctx.  `stream0`/`stream1` are torch.cuda.Stream objects (or None for the default)."""
+def upload_weights(w: Dict[str, np.ndarray], dtype: str) -> Dict[str, DeviceArray]:
+    return {k: DeviceArray.from_numpy(v, dtype) for k, v in w.items()}
 
-    def __init__(self, cfg: IsoCfg, stream0=None, stream1=None):
+
+class Context:
+    """Owns an iso_ctx.  `stream0`/`stream1`: Stream objects (created here if omitted)."""
+
+    def __init__(self, cfg: IsoCfg, stream0=None, stream1=None, two_streams: bool = True):
         self._lib = load()
         self.cfg = cfg
-        self.stream0, self.stream1 = stream0, stream1   # keep the torch streams alive
+        if stream0 is None:
+            stream0 = Stream()
+        if stream1 is None:
+            stream1 = Stream() if two_streams else stream0
+        self.stream0, self.stream1 = stream0, stream1   # keep the streams alive
         handle = ctypes.c_void_p()
         _check(self._lib.iso_create(ctypes.byref(handle), ctypes.byref(cfg), _stream_handle(stream0),
                                     _stream_handle(stream1)))
@@ -198,13 +354,13 @@ class Context:
     def host_sink(self) -> int:
         return self._lib.iso_host_sink(self._h)
 
-    def layer_prefill(self, w: Dict[str, torch.Tensor], x, k_cache, v_cache, T: int, split: int,
+    def layer_prefill(self, w: Dict[str, object], x, k_cache, v_cache, T: int, split: int,
                       comm: int = ISO_COMM_NONE, sched: int = ISO_SCHED_OVERLAP) -> None:
         ws = pack_weights(w)
         _check(self._lib.iso_layer_prefill(self._h, ctypes.byref(ws), _ptr(x), _ptr(k_cache), _ptr(v_cache),
                                            T, split, comm, sched))
 
-    def stack_prefill(self, layers: Sequence[Dict[str, torch.Tensor]], x, k_caches, v_caches, T: int, split: int,
+    def stack_prefill(self, layers: Sequence[Dict[str, object]], x, k_caches, v_caches, T: int, split: int,
                       comm: int = ISO_COMM_NONE, sched: int = ISO_SCHED_OVERLAP) -> None:
         arr = (IsoWeights * len(layers))(*[pack_weights(w) for w in layers])
         _check(self._lib.iso_stack_prefill(self._h, arr, len(layers), _ptr(x), _ptr(k_caches), _ptr(v_caches),

@@ -26,13 +26,41 @@ template <typename T> __device__ __forceinline__ void store16(T *p, const float 
     *reinterpret_cast<uint4 *>(p) = raw;
 }
 
+// Loads VEC consecutive elements as floats from a buffer of T or of float.
+template <typename T, bool F32> __device__ __forceinline__ void load_vec(const void *base, size_t idx,
+                                                                          float (&out)[16 / sizeof(T)]) {
+    constexpr int VEC = 16 / sizeof(T);
+    if (F32) {
+        const float *p = reinterpret_cast<const float *>(base) + idx;
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(p + i);
+            out[i] = v.x; out[i + 1] = v.y; out[i + 2] = v.z; out[i + 3] = v.w;
+        }
+    } else {
+        load16<T>(reinterpret_cast<const T *>(base) + idx, out);
+    }
+}
+template <typename T, bool F32> __device__ __forceinline__ void store_vec(void *base, size_t idx,
+                                                                           const float (&in)[16 / sizeof(T)]) {
+    constexpr int VEC = 16 / sizeof(T);
+    if (F32) {
+        float *p = reinterpret_cast<float *>(base) + idx;
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) *reinterpret_cast<float4 *>(p + i) = make_float4(in[i], in[i + 1], in[i + 2], in[i + 3]);
+    } else {
+        store16<T>(reinterpret_cast<T *>(base) + idx, in);
+    }
+}
+
 // One 256-thread workgroup per token row.  x_new = x (+ delta); optionally written back; optionally
 // y = x_new * rsqrt(mean(x_new^2) + eps) * g.  The first CACHE vectors of each thread stay in
 // registers between the reduction and the scaling, so rows up to 256*CACHE*VEC elements are read once.
-template <typename T, bool HAS_DELTA, bool WRITE_Y>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const T *__restrict__ delta,
-                                                      T *x_out, const T *__restrict__ g, T *__restrict__ y,
-                                                      int H, float eps) {
+// XIN_F32 / XOUT_F32: the residual stream is read from / written to an fp32 side buffer instead of the
+// T-typed one (the bf16 layer keeps its mid-layer residual unrounded between the two blocks).
+template <typename T, bool HAS_DELTA, bool WRITE_Y, bool XIN_F32, bool XOUT_F32>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const void *x, const T *__restrict__ delta, void *x_out,
+                                                      const T *__restrict__ g, T *__restrict__ y, int H, float eps) {
     constexpr int VEC = 16 / sizeof(T);
     constexpr int CACHE = 4;
     const int tid = threadIdx.x;
@@ -44,13 +72,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const T *__res
     for (int c = 0; c < CACHE; ++c) {
         const int idx = tid + c * 256;
         if (idx < nvec) {
-            load16<T>(x + row + (size_t)idx * VEC, vals[c]);
+            load_vec<T, XIN_F32>(x, row + (size_t)idx * VEC, vals[c]);
             if (HAS_DELTA) {
                 float dv[VEC];
                 load16<T>(delta + row + (size_t)idx * VEC, dv);
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) vals[c][i] += dv[i];
-                store16<T>(x_out + row + (size_t)idx * VEC, vals[c]);
+                store_vec<T, XOUT_F32>(x_out, row + (size_t)idx * VEC, vals[c]);
             }
 #pragma unroll
             for (int i = 0; i < VEC; ++i) ss += vals[c][i] * vals[c][i];
@@ -58,13 +86,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const T *__res
     }
     for (int idx = tid + CACHE * 256; idx < nvec; idx += 256) {
         float xv[VEC];
-        load16<T>(x + row + (size_t)idx * VEC, xv);
+        load_vec<T, XIN_F32>(x, row + (size_t)idx * VEC, xv);
         if (HAS_DELTA) {
             float dv[VEC];
             load16<T>(delta + row + (size_t)idx * VEC, dv);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) xv[i] += dv[i];
-            store16<T>(x_out + row + (size_t)idx * VEC, xv);
+            store_vec<T, XOUT_F32>(x_out, row + (size_t)idx * VEC, xv);
         }
 #pragma unroll
         for (int i = 0; i < VEC; ++i) ss += xv[i] * xv[i];
@@ -92,7 +120,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const T *__res
     for (int idx = tid + CACHE * 256; idx < nvec; idx += 256) {
         // beyond the register cache: re-read the (already updated) row
         float xv[VEC], gv[VEC];
-        load16<T>((HAS_DELTA ? (const T *)x_out : x) + row + (size_t)idx * VEC, xv);
+        if (HAS_DELTA) load_vec<T, XOUT_F32>(x_out, row + (size_t)idx * VEC, xv);
+        else load_vec<T, XIN_F32>(x, row + (size_t)idx * VEC, xv);
         load16<T>(g + (size_t)idx * VEC, gv);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) gv[i] = xv[i] * scale * gv[i];
@@ -163,27 +192,28 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T *__restrict__ gu, T
     }
 }
 
-template <typename T>
+template <typename T, bool XIN_F32, bool XOUT_F32>
 hipError_t rmsnorm_dispatch(const void *x, const void *delta, void *x_out, const void *g, void *y, int T_, int H,
                             float eps, hipStream_t s) {
     dim3 grid(T_), block(256);
-    const T *xp = (const T *)x;
     const T *dp = (const T *)delta;
     if (delta && y)
-        hipLaunchKernelGGL((rmsnorm_kernel<T, true, true>), grid, block, 0, s, xp, dp, (T *)x_out, (const T *)g, (T *)y, H, eps);
+        hipLaunchKernelGGL((rmsnorm_kernel<T, true, true, XIN_F32, XOUT_F32>), grid, block, 0, s, x, dp, x_out, (const T *)g, (T *)y, H, eps);
     else if (delta)
-        hipLaunchKernelGGL((rmsnorm_kernel<T, true, false>), grid, block, 0, s, xp, dp, (T *)x_out, (const T *)g, (T *)y, H, eps);
+        hipLaunchKernelGGL((rmsnorm_kernel<T, true, false, XIN_F32, XOUT_F32>), grid, block, 0, s, x, dp, x_out, (const T *)g, (T *)y, H, eps);
     else
-        hipLaunchKernelGGL((rmsnorm_kernel<T, false, true>), grid, block, 0, s, xp, dp, (T *)x_out, (const T *)g, (T *)y, H, eps);
+        hipLaunchKernelGGL((rmsnorm_kernel<T, false, true, XIN_F32, XOUT_F32>), grid, block, 0, s, x, dp, x_out, (const T *)g, (T *)y, H, eps);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta, void *x_out, const void *g, void *y,
-                              int T, int H, float eps, hipStream_t s) {
-    if (dtype == ISO_F32) return rmsnorm_dispatch<float>(x, delta, x_out, g, y, T, H, eps, s);
-    return rmsnorm_dispatch<bf16_t>(x, delta, x_out, g, y, T, H, eps, s);
+                              int T, int H, float eps, int x_in_f32, int x_out_f32, hipStream_t s) {
+    if (dtype == ISO_F32) return rmsnorm_dispatch<float, false, false>(x, delta, x_out, g, y, T, H, eps, s);
+    if (x_in_f32) return rmsnorm_dispatch<bf16_t, true, false>(x, delta, x_out, g, y, T, H, eps, s);
+    if (x_out_f32) return rmsnorm_dispatch<bf16_t, false, true>(x, delta, x_out, g, y, T, H, eps, s);
+    return rmsnorm_dispatch<bf16_t, false, false>(x, delta, x_out, g, y, T, H, eps, s);
 }
 
 hipError_t iso_launch_rope_kv(int dtype, void *qkv, void *k_cache, void *v_cache, const float *cos_t,

@@ -42,7 +42,12 @@ template <int BM, int BN, int WM, int WN> struct DtlCfg {
     static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "wave-loads must divide evenly");
 };
 
-template <int BM, int BN, int WM, int WN, int SWZ>
+// SWIGLU = true: W is the [2F, K] gate/up matrix (gate rows first) and the kernel writes
+// act[M, F] = silu(gate) * up directly.  The W tile is assembled so that, inside every wave, the MFMA column
+// blocks alternate gate / up for the same 32 MLP columns; a lane then holds gate and up of one output element
+// in the same register slot of two neighbouring accumulators and the activation needs no data exchange and
+// no rounding of the projection output.  N is 2F and the output row stride is F.
+template <int BM, int BN, int WM, int WN, int SWZ, bool SWIGLU>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_t *__restrict__ A,
                                                                      const bf16_t *__restrict__ W,
                                                                      bf16_t *__restrict__ C, int M, int N, int K,
@@ -89,7 +94,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
     for (int i = 0; i < W_LOADS; ++i) {
         const int r = (wave + NWAVES * i) * 8 + ld_row;
         const int chunk = ld_slot ^ swz<SWZ>(r);
-        w_off[i] = ((uint32_t)min(n0 + r, N - 1) * (uint32_t)K + chunk * 8) * 2u;
+        int grow;
+        if (SWIGLU) {
+            const int F = N / 2;
+            const int jt = (r % Cfg::WTN) / 32;          // MFMA column block inside the wave tile
+            const int f = tile_n * (BN / 2) + (r / Cfg::WTN) * (Cfg::WTN / 2) + (jt / 2) * 32 + (r % 32);
+            grow = (jt & 1) * F + min(f, F - 1);
+        } else {
+            grow = min(n0 + r, N - 1);
+        }
+        w_off[i] = ((uint32_t)grow * (uint32_t)K + chunk * 8) * 2u;
     }
     auto issue = [&](int stage, int k0) {
         unsigned char *base = lds + stage * STAGE;
@@ -177,33 +191,62 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
     //      32x32 tile.  Each wave parks its tile as bf16 in its own LDS region, then streams it out in
     //      16-byte pieces so that every store instruction covers whole 256-byte row segments.
     __syncthreads();                         // every wave is done reading operand tiles
-    bf16_t *ct = reinterpret_cast<bf16_t *>(lds) + (size_t)wave * Cfg::WTM * Cfg::CP;
+    if (!SWIGLU) {
+        bf16_t *ct = reinterpret_cast<bf16_t *>(lds) + (size_t)wave * Cfg::WTM * Cfg::CP;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * Cfg::CP + j * 32 + lrow] = (bf16_t)acc[i][j][r];
-    // only this wave reads what it wrote: LDS accesses of one wave are ordered, no barrier needed
-    constexpr int CPR = Cfg::WTN / 8;        // 16-byte pieces per row
-    constexpr int PIECES = Cfg::WTM * CPR;
-    const int gm0 = m0 + wm * Cfg::WTM, gn0 = n0 + wn * Cfg::WTN;
+                for (int r = 0; r < 16; ++r)
+                    ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * Cfg::CP + j * 32 + lrow] = (bf16_t)acc[i][j][r];
+        // only this wave reads what it wrote: LDS accesses of one wave are ordered, no barrier needed
+        constexpr int CPR = Cfg::WTN / 8;        // 16-byte pieces per row
+        constexpr int PIECES = Cfg::WTM * CPR;
+        const int gm0 = m0 + wm * Cfg::WTM, gn0 = n0 + wn * Cfg::WTN;
 #pragma unroll
-    for (int p = lane; p < PIECES; p += 64) {
-        const int row = p / CPR, cc = (p % CPR) * 8;
-        const int gm = gm0 + row, gn = gn0 + cc;
-        if (gm < M && gn < N)                // N % 8 == 0: a piece is entirely inside or outside
-            *reinterpret_cast<uint4 *>(C + (size_t)gm * N + gn) = *reinterpret_cast<const uint4 *>(ct + row * Cfg::CP + cc);
+        for (int p = lane; p < PIECES; p += 64) {
+            const int row = p / CPR, cc = (p % CPR) * 8;
+            const int gm = gm0 + row, gn = gn0 + cc;
+            if (gm < M && gn < N)                // N % 8 == 0: a piece is entirely inside or outside
+                *reinterpret_cast<uint4 *>(C + (size_t)gm * N + gn) =
+                    *reinterpret_cast<const uint4 *>(ct + row * Cfg::CP + cc);
+        }
+    } else {
+        constexpr int HW = Cfg::WTN / 2;         // output columns per wave
+        constexpr int HP = HW + 8;               // LDS pitch
+        const int F = N / 2;
+        bf16_t *ct = reinterpret_cast<bf16_t *>(lds) + (size_t)wave * Cfg::WTM * HP;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int jp = 0; jp < TN / 2; ++jp)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float g = acc[i][2 * jp][r], u = acc[i][2 * jp + 1][r];
+                    const float a = g / (1.0f + __expf(-g)) * u;
+                    ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * HP + jp * 32 + lrow] = (bf16_t)a;
+                }
+        constexpr int CPR = HW / 8;
+        constexpr int PIECES = Cfg::WTM * CPR;
+        const int gm0 = m0 + wm * Cfg::WTM, gf0 = tile_n * (BN / 2) + wn * HW;
+#pragma unroll
+        for (int p = lane; p < PIECES; p += 64) {
+            const int row = p / CPR, cc = (p % CPR) * 8;
+            const int gm = gm0 + row, gf = gf0 + cc;
+            if (gm < M && gf < F)                // F % 8 == 0
+                *reinterpret_cast<uint4 *>(C + (size_t)gm * F + gf) =
+                    *reinterpret_cast<const uint4 *>(ct + row * HP + cc);
+        }
     }
 #endif
 }
 
-template <int BM, int BN, int WM, int WN, int SWZ>
+template <int BM, int BN, int WM, int WN, int SWZ, bool SWIGLU>
 hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     using Cfg = DtlCfg<BM, BN, WM, WN>;
     static bool attr_set = false;
-    auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWZ>;
+    auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWZ, SWIGLU>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
@@ -224,26 +267,31 @@ bool iso_gemm_bf16_dtl_supported(int M, int N, int K) {
            (long long)N * K < (1ll << 31);
 }
 
+// Tile shape: fewest "rounds" over the 256 compute units, larger tiles preferred on ties.
+static int pick_variant(int M, int N) {
+    const int cand[4][3] = {{256, 256, 1}, {256, 128, 2}, {128, 256, 4}, {128, 128, 3}};
+    const double eff[4] = {1.0, 0.92, 0.92, 0.8};
+    double best = 1e300;
+    int v = 1;
+    for (int i = 0; i < 4; ++i) {
+        const long long tiles = (long long)((M + cand[i][0] - 1) / cand[i][0]) * ((N + cand[i][1] - 1) / cand[i][1]);
+        const long long rounds = (tiles + 255) / 256;
+        const double cost = (double)rounds * cand[i][0] * cand[i][1] / eff[i];
+        if (cost < best) { best = cost; v = cand[i][2]; }
+    }
+    return v;
+}
+
 // variant: 0 = pick by shape; 1 = 256x256 8 waves, 2 = 256x128 8 waves, 3 = 128x128 4 waves, 4 = 128x256 8 waves,
 //          5 = 256x256 4 waves; +8 selects the other LDS swizzle
 hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M, int N, int K, int variant,
                                     hipStream_t s) {
     int v = variant & 7;
     const int sw = (variant >> 3) & 1;
-    if (v == 0) {
-        // fewest "rounds" over the 256 compute units, larger tiles preferred on ties
-        const int cand[4][3] = {{256, 256, 1}, {256, 128, 2}, {128, 256, 4}, {128, 128, 3}};
-        const double eff[4] = {1.0, 0.92, 0.92, 0.8};
-        double best = 1e300;
-        for (int i = 0; i < 4; ++i) {
-            const long long tiles = (long long)((M + cand[i][0] - 1) / cand[i][0]) * ((N + cand[i][1] - 1) / cand[i][1]);
-            const long long rounds = (tiles + 255) / 256;
-            const double cost = (double)rounds * cand[i][0] * cand[i][1] / eff[i];
-            if (cost < best) { best = cost; v = cand[i][2]; }
-        }
-    }
+    if (v == 0) v = pick_variant(M, N);
 #define ISO_DTL(BM_, BN_, WM_, WN_)                                                          \
-    return sw ? launch<BM_, BN_, WM_, WN_, 0>(a, w, c, M, N, K, s) : launch<BM_, BN_, WM_, WN_, 1>(a, w, c, M, N, K, s)
+    return sw ? launch<BM_, BN_, WM_, WN_, 0, false>(a, w, c, M, N, K, s)                    \
+              : launch<BM_, BN_, WM_, WN_, 1, false>(a, w, c, M, N, K, s)
     switch (v) {
         case 1: ISO_DTL(256, 256, 4, 2);
         case 2: ISO_DTL(256, 128, 4, 2);
@@ -252,4 +300,21 @@ hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M
         default: ISO_DTL(128, 128, 2, 2);
     }
 #undef ISO_DTL
+}
+
+// act[M, F] = silu(a w_gate^T) * (a w_up^T) with w = [gate; up] of shape [2F, K].
+bool iso_gemm_swiglu_bf16_supported(int M, int F, int K) {
+    return iso_gemm_bf16_dtl_supported(M, 2 * F, K) && (F % 8) == 0;
+}
+
+hipError_t iso_launch_gemm_swiglu_bf16(const void *a, const void *w, void *act, int M, int F, int K, int variant,
+                                       hipStream_t s) {
+    int v = variant & 7;
+    if (v == 0) v = pick_variant(M, 2 * F);
+    switch (v) {
+        case 1: return launch<256, 256, 4, 2, 1, true>(a, w, act, M, 2 * F, K, s);
+        case 2: return launch<256, 128, 4, 2, 1, true>(a, w, act, M, 2 * F, K, s);
+        case 4: return launch<128, 256, 2, 4, 1, true>(a, w, act, M, 2 * F, K, s);
+        default: return launch<128, 128, 2, 2, 1, true>(a, w, act, M, 2 * F, K, s);
+    }
 }

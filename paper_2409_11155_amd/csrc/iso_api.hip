@@ -40,7 +40,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 int n_qkv(const iso_cfg &c) { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
 
 struct WsLayout {
-    size_t y, qkv, attn, part, gu, act, total;
+    size_t y, qkv, attn, part, gu, act, x1f, total;
 };
 
 WsLayout ws_layout(const iso_cfg &c) {
@@ -54,6 +54,7 @@ WsLayout ws_layout(const iso_cfg &c) {
     l.part = take(t * c.hidden);
     l.gu = take(t * 2 * c.ffn);
     l.act = take(t * c.ffn);
+    l.x1f = take(c.dtype == ISO_BF16 ? t * c.hidden * 2 : 0);   // fp32 = two bf16 slots per element
     l.total = off;
     return l;
 }
@@ -152,10 +153,12 @@ int attn_block_head(iso_ctx *ctx, const iso_weights *w, void *x, void *kc, void 
     char *xr = at(x, ck.lo, H, e);
     char *yr = at(ctx->y, ck.lo, H, e);
     char *qkvr = at(ctx->qkv, ck.lo, NQKV, e);
-    if (add_prev_partial)
-        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, at(ctx->part, ck.lo, H, e), xr, w->g_attn, yr, ck.n, H, c.rms_eps, ck.s), "residual+rmsnorm");
+    const bool hi = c.dtype == ISO_BF16;     // mid-layer residual lives in the fp32 side buffer
+    if (add_prev_partial)   // x = x1 + (previous layer's MLP partial), y = norm(x)
+        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, hi ? (void *)(ctx->x1f + (size_t)ck.lo * H) : (void *)xr,
+                   at(ctx->part, ck.lo, H, e), xr, w->g_attn, yr, ck.n, H, c.rms_eps, hi, 0, ck.s), "residual+rmsnorm");
     else
-        LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, nullptr, nullptr, w->g_attn, yr, ck.n, H, c.rms_eps, ck.s), "rmsnorm");
+        LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, nullptr, nullptr, w->g_attn, yr, ck.n, H, c.rms_eps, 0, 0, ck.s), "rmsnorm");
     ISO_TRY(gemm(ctx, ISO_K_GEMM_QKV, yr, w->w_qkv, qkvr, ck.n, NQKV, H, ck.s));
     LAUNCH_TRY(ISO_K_ROPE_KV, ck.s, iso_launch_rope_kv(c.dtype, qkvr, kc, vc, ctx->rope_cos, ctx->rope_sin, ck.n, ck.lo, c.n_q_heads,
                                   c.n_kv_heads, c.head_dim, ck.s), "rope+kv");
@@ -187,9 +190,20 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
     char *partr = at(ctx->part, ck.lo, H, e);
     char *gur = at(ctx->gu, ck.lo, 2 * (size_t)F, e);
     char *actr = at(ctx->act, ck.lo, F, e);
-    LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, partr, xr, w->g_mlp, yr, ck.n, H, c.rms_eps, ck.s), "residual+rmsnorm");
-    ISO_TRY(gemm(ctx, ISO_K_GEMM_GATE_UP, yr, w->w_gate_up, gur, ck.n, 2 * F, H, ck.s));
-    LAUNCH_TRY(ISO_K_SWIGLU, ck.s, iso_launch_swiglu(c.dtype, gur, actr, ck.n, F, ck.s), "swiglu");
+    const bool hi = c.dtype == ISO_BF16;
+    // x1 = x + (attention partial); y = norm(x1).  bf16 layers keep x1 unrounded in the fp32 side buffer.
+    LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, partr, hi ? (void *)(ctx->x1f + (size_t)ck.lo * H) : (void *)xr,
+               w->g_mlp, yr, ck.n, H, c.rms_eps, 0, hi, ck.s), "residual+rmsnorm");
+    const bool fused = c.dtype == ISO_BF16 && !(ctx->flags & (ISO_FLAG_SIMPLE_GEMM | ISO_FLAG_GEMM_STAGED | ISO_FLAG_NO_FUSE)) &&
+                       iso_gemm_swiglu_bf16_supported(ck.n, F, H);
+    if (fused) {   // gate/up projection with the activation in its epilogue: the [Tc, 2F] tensor never exists
+        Timed t_(ctx, ISO_K_GEMM_GATE_UP, ck.s);
+        hipError_t e_ = iso_launch_gemm_swiglu_bf16(yr, w->w_gate_up, actr, ck.n, F, H, (ctx->flags >> 8) & 15, ck.s);
+        if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "gate/up+swiglu launch: %s", hipGetErrorString(e_));
+    } else {
+        ISO_TRY(gemm(ctx, ISO_K_GEMM_GATE_UP, yr, w->w_gate_up, gur, ck.n, 2 * F, H, ck.s));
+        LAUNCH_TRY(ISO_K_SWIGLU, ck.s, iso_launch_swiglu(c.dtype, gur, actr, ck.n, F, ck.s), "swiglu");
+    }
     ISO_TRY(gemm(ctx, ISO_K_GEMM_DOWN, actr, w->w_down, partr, ck.n, H, F, ck.s));
     if (comm == ISO_COMM_D2H) {
         Timed t_(ctx, ISO_K_COMM, ck.s);
@@ -203,8 +217,9 @@ int final_residual(iso_ctx *ctx, void *x, const Chunk &ck) {
     const iso_cfg &c = ctx->cfg;
     const size_t e = ctx->elt;
     char *xr = at(x, ck.lo, c.hidden, e);
-    LAUNCH_TRY(ISO_K_RESIDUAL, ck.s, iso_launch_rmsnorm(c.dtype, xr, at(ctx->part, ck.lo, c.hidden, e), xr, nullptr, nullptr, ck.n, c.hidden,
-                                  c.rms_eps, ck.s), "residual");
+    const bool hi = c.dtype == ISO_BF16;
+    LAUNCH_TRY(ISO_K_RESIDUAL, ck.s, iso_launch_rmsnorm(c.dtype, hi ? (void *)(ctx->x1f + (size_t)ck.lo * c.hidden) : (void *)xr,
+               at(ctx->part, ck.lo, c.hidden, e), xr, nullptr, nullptr, ck.n, c.hidden, c.rms_eps, hi, 0, ck.s), "residual");
     return ISO_OK;
 }
 
@@ -324,6 +339,7 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
         char *b = (char *)ctx->ws;
         ctx->y = b + l.y; ctx->qkv = b + l.qkv; ctx->attn = b + l.attn;
         ctx->part = b + l.part; ctx->gu = b + l.gu; ctx->act = b + l.act;
+        ctx->x1f = (float *)(b + l.x1f);
         if (!hip_ok(hipMalloc((void **)&ctx->rope_cos, table * sizeof(float)), "hipMalloc(rope cos)")) break;
         if (!hip_ok(hipMalloc((void **)&ctx->rope_sin, table * sizeof(float)), "hipMalloc(rope sin)")) break;
         {   // rotary table: angles in double on the host, stored as fp32
@@ -418,6 +434,62 @@ int iso_timing_read(iso_ctx *ctx, int kind, double *total_ms, int *launches) {
     return ISO_OK;
 }
 
+int iso_device_count(int *count) {
+    if (!count) return fail(ISO_ERR_NULL, "count is NULL");
+    *count = 0;
+    hipError_t e = hipGetDeviceCount(count);
+    if (e == hipErrorNoDevice || e == hipErrorInsufficientDriver) { *count = 0; (void)hipGetLastError(); return ISO_OK; }
+    if (e != hipSuccess) { *count = 0; return fail(ISO_ERR_HIP, "hipGetDeviceCount: %s", hipGetErrorString(e)); }
+    return ISO_OK;
+}
+int iso_device_sync(void) { HIP_TRY(hipDeviceSynchronize()); return ISO_OK; }
+int iso_dev_alloc(void **ptr, size_t bytes) {
+    if (!ptr) return fail(ISO_ERR_NULL, "ptr is NULL");
+    *ptr = nullptr;
+    HIP_TRY(hipMalloc(ptr, bytes ? bytes : 1));
+    return ISO_OK;
+}
+int iso_dev_free(void *ptr) { if (ptr) HIP_TRY(hipFree(ptr)); return ISO_OK; }
+int iso_dev_fill(void *ptr, int byte_value, size_t bytes) {
+    if (!ptr) return fail(ISO_ERR_NULL, "ptr is NULL");
+    HIP_TRY(hipMemset(ptr, byte_value, bytes));
+    HIP_TRY(hipDeviceSynchronize());
+    return ISO_OK;
+}
+int iso_host_alloc(void **ptr, size_t bytes) {
+    if (!ptr) return fail(ISO_ERR_NULL, "ptr is NULL");
+    *ptr = nullptr;
+    HIP_TRY(hipHostMalloc(ptr, bytes ? bytes : 1, hipHostMallocDefault));
+    return ISO_OK;
+}
+int iso_host_free(void *ptr) { if (ptr) HIP_TRY(hipHostFree(ptr)); return ISO_OK; }
+int iso_copy_h2d(void *dst, const void *src, size_t bytes) {
+    if (!dst || !src) return fail(ISO_ERR_NULL, "dst and src must be non-NULL");
+    HIP_TRY(hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice));
+    return ISO_OK;
+}
+int iso_copy_d2h(void *dst, const void *src, size_t bytes) {
+    if (!dst || !src) return fail(ISO_ERR_NULL, "dst and src must be non-NULL");
+    HIP_TRY(hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost));
+    return ISO_OK;
+}
+int iso_copy_d2d(void *dst, const void *src, size_t bytes) {
+    if (!dst || !src) return fail(ISO_ERR_NULL, "dst and src must be non-NULL");
+    HIP_TRY(hipMemcpy(dst, src, bytes, hipMemcpyDeviceToDevice));
+    return ISO_OK;
+}
+int iso_stream_create(void **stream) {
+    if (!stream) return fail(ISO_ERR_NULL, "stream is NULL");
+    hipStream_t s = nullptr;
+    HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+    *stream = (void *)s;
+    return ISO_OK;
+}
+int iso_stream_destroy(void *stream) {
+    if (stream) HIP_TRY(hipStreamDestroy((hipStream_t)stream));
+    return ISO_OK;
+}
+
 void *iso_host_sink(iso_ctx *ctx) { return ctx ? ctx->host_sink : nullptr; }
 
 int iso_layer_prefill(iso_ctx *ctx, const iso_weights *w, void *x, void *k_cache, void *v_cache, int T, int split,
@@ -464,7 +536,7 @@ int iso_rmsnorm(iso_ctx *ctx, const void *x, const void *g, void *y, int T, void
     if (!x || !g || !y) return fail(ISO_ERR_NULL, "x, g and y must be non-NULL");
     if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
     LAUNCH_TRY(ISO_K_RMSNORM, (hipStream_t)stream, iso_launch_rmsnorm(ctx->cfg.dtype, x, nullptr, nullptr, g, y, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
-                                  (hipStream_t)stream), "rmsnorm");
+                                  0, 0, (hipStream_t)stream), "rmsnorm");
     return ISO_OK;
 }
 
@@ -474,7 +546,7 @@ int iso_residual_rmsnorm(iso_ctx *ctx, void *x, const void *delta, const void *g
     if ((y != nullptr) != (g != nullptr)) return fail(ISO_ERR_NULL, "g and y must both be given or both be NULL");
     if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
     LAUNCH_TRY(y ? ISO_K_RESID_NORM : ISO_K_RESIDUAL, (hipStream_t)stream, iso_launch_rmsnorm(ctx->cfg.dtype, x, delta, x, g, y, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
-                                  (hipStream_t)stream), "residual+rmsnorm");
+                                  0, 0, (hipStream_t)stream), "residual+rmsnorm");
     return ISO_OK;
 }
 

@@ -29,6 +29,7 @@ struct iso_ctx {
     void *part;        // [max_seq, hidden]   row-parallel partial (o_proj, then down)
     void *gu;          // [max_seq, 2*ffn]
     void *act;         // [max_seq, ffn]
+    float *x1f;        // [max_seq, hidden] fp32: residual stream between the two blocks of a bf16 layer
     float *rope_cos;   // [max_seq, d/2]
     float *rope_sin;   // [max_seq, d/2]
     void *host_sink;   // pinned, 2 * max_seq * hidden elements
@@ -42,7 +43,8 @@ constexpr int ISO_MAX_TIMED = 8192;
 
 // ---- launchers; each validates nothing (callers do) and returns the launch status -------------
 hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta_or_null, void *x_out_or_null,
-                              const void *g, void *y_or_null, int T, int H, float eps, hipStream_t s);
+                              const void *g, void *y_or_null, int T, int H, float eps, int x_in_f32, int x_out_f32,
+                              hipStream_t s);   // x_in_f32 / x_out_f32: bf16 layers only, residual in an fp32 side buffer
 hipError_t iso_launch_rope_kv(int dtype, void *qkv, void *k_cache, void *v_cache, const float *cos_t,
                               const float *sin_t, int Tc, int q_offset, int nq, int nkv, int d, hipStream_t s);
 hipError_t iso_launch_swiglu(int dtype, const void *gu, void *a, int T, int F, hipStream_t s);
@@ -53,6 +55,9 @@ bool iso_gemm_bf16_mfma_supported(int M, int N, int K);
 hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M, int N, int K, int variant,
                                     hipStream_t s);
 bool iso_gemm_bf16_dtl_supported(int M, int N, int K);
+hipError_t iso_launch_gemm_swiglu_bf16(const void *a, const void *w, void *act, int M, int F, int K, int variant,
+                                       hipStream_t s);
+bool iso_gemm_swiglu_bf16_supported(int M, int F, int K);
 hipError_t iso_launch_attn_simple(int dtype, const void *q, const void *k, const void *v, void *out, int Tc,
                                   int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
 hipError_t iso_launch_attn_bf16_mfma(const void *q, const void *k, const void *v, void *out, int Tc,

@@ -14,8 +14,8 @@ def pytest_configure(config):
 
 def _have_gpu() -> bool:
     try:
-        import torch
-        return torch.cuda.is_available()
+        import paper_2409_11155_amd as iso
+        return iso.device_count() > 0
     except Exception:
         return False
 

@@ -21,8 +21,8 @@ def main():
     wl = iso_inputs.WORKLOADS["tiny_f32"]
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
     sh = orc.LayerShape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.rms_eps, wl.rope_base)
-    wn = {k: v.double().numpy() for k, v in w.items()}
-    out = orc.layer_unsplit(x.double().numpy(), wn, sh)["x_out"]
+    wn = {k: iso_inputs.to_f64(v, wl.dtype) for k, v in w.items()}
+    out = orc.layer_unsplit(iso_inputs.to_f64(x, wl.dtype), wn, sh)["x_out"]
     samples = [(r, c, float(out[r, c])) for r in (0, 1, 63, 64, 65, 127) for c in (0, 17, 255)]
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tiny_f32_oracle.json")
     with open(path, "w") as f:

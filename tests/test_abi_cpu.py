@@ -5,7 +5,6 @@ import os
 import re
 
 import pytest
-import torch
 
 import paper_2409_11155_amd as iso
 
@@ -89,8 +88,20 @@ def test_null_context_and_null_out_are_refused_without_touching_a_device():
     assert handle.value is None          # *out is cleared on failure
 
 
-@pytest.mark.skipif(torch.cuda.is_available(), reason="checks the no-device error path")
+@pytest.mark.skipif(iso.device_count() > 0, reason="checks the no-device error path")
 def test_create_without_a_device_reports_a_hip_error():
     with pytest.raises(iso.IsoError) as ei:
         iso.Context(_good_cfg())
     assert ei.value.code == iso.ISO_ERR_HIP
+
+
+@pytest.mark.skipif(iso.device_count() > 0, reason="checks the no-device error path")
+def test_plumbing_without_a_device_reports_errors_not_crashes():
+    lib = iso.load()
+    assert iso.device_count() == 0
+    p = ctypes.c_void_p(77)
+    assert lib.iso_dev_alloc(ctypes.byref(p), 16) == iso.ISO_ERR_HIP and p.value is None
+    assert lib.iso_dev_alloc(None, 16) == iso.ISO_ERR_NULL
+    assert lib.iso_stream_create(None) == iso.ISO_ERR_NULL
+    assert lib.iso_copy_h2d(None, None, 4) == iso.ISO_ERR_NULL
+    assert lib.iso_dev_free(None) == iso.ISO_OK and lib.iso_host_free(None) == iso.ISO_OK

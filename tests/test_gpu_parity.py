@@ -8,21 +8,29 @@ Tolerances (metric: max |got - ref| / max(|ref|, rms(ref)), see oracle.max_rel_e
 """
 import numpy as np
 import pytest
-import torch
 
+import paper_2409_11155_amd as iso      # first: binds libiso to the HIP runtime it was built against
 import iso_inputs
-import paper_2409_11155_amd as iso
 from oracle import iso_oracle as orc
 
 pytestmark = pytest.mark.gpu
 
 TOL_LAYER = {"f32": 1e-4, "bf16": 2e-2}
 TOL_STEP = {"f32": 2e-5, "bf16": 1e-2}
-DEV = "cuda:0"
+NAN_BYTE = 0xFF        # 0xFFFF (bf16) and 0xFFFFFFFF (fp32) are NaN bit patterns
 
 
-def f64(t: torch.Tensor) -> np.ndarray:
-    return t.detach().to("cpu", torch.float64).numpy()
+def dev(a, dt):
+    return iso.DeviceArray.from_numpy(a, dt)
+
+
+def f64(buf):
+    """float64 values of a DeviceArray (downloaded) or of a host storage array given its dtype."""
+    return iso_inputs.to_f64(buf.numpy(), buf.dtype)
+
+
+def h64(a, dt):
+    return iso_inputs.to_f64(a, dt)
 
 
 def shape_of(hidden, nq, nkv, d, ffn, eps=1e-6, base=10000.0):
@@ -31,110 +39,103 @@ def shape_of(hidden, nq, nkv, d, ffn, eps=1e-6, base=10000.0):
 
 def make_ctx(hidden, nq, nkv, d, ffn, dtype, max_seq, two_streams=True):
     cfg = iso.make_cfg(hidden, nq, nkv, d, ffn, dtype, max_seq)
-    s0 = torch.cuda.Stream(device=DEV)
-    s1 = torch.cuda.Stream(device=DEV) if two_streams else s0
-    return iso.Context(cfg, s0, s1)
-
-
-def dtype_name(dt):
-    return "f32" if dt == torch.float32 else "bf16"
+    return iso.Context(cfg, two_streams=two_streams)
 
 
 # ------------------------------------------------------------------------------ element-wise steps
 
-@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("T,H", [(1, 256), (37, 1000), (130, 8192), (5, 16384)])
 def test_rmsnorm_and_residual_rmsnorm(dt, T, H):
-    torch.manual_seed(T * 7 + H)
-    x = torch.randn(T, H).to(dt)
-    delta = (0.5 * torch.randn(T, H)).to(dt)
-    g = (1 + 0.1 * torch.randn(H)).to(dt)
+    x = iso_inputs.randn((T, H), seed=T * 7 + H, dtype=dt)
+    delta = iso_inputs.randn((T, H), seed=T * 7 + H + 1, dtype=dt, scale=0.5)
+    g = iso_inputs.store(1 + 0.1 * iso_inputs.bf16_bits_to_f32(iso_inputs.randn((H,), seed=H, dtype="bf16")), dt)
     with make_ctx(H, 4, 4, 64, 64, dt, 256) as ctx:
-        xd, dd, gd = x.to(DEV), delta.to(DEV), g.to(DEV)
-        y = torch.empty_like(xd)
+        xd, dd, gd = dev(x, dt), dev(delta, dt), dev(g, dt)
+        y = iso.DeviceArray((T, H), dt)
         ctx.rmsnorm(xd, gd, y, T, ctx.stream0)
         ctx.sync()
-        tol = TOL_STEP[dtype_name(dt)]
-        assert orc.max_rel_err(f64(y), orc.rmsnorm(f64(x), f64(g), 1e-6)) <= tol
+        tol = TOL_STEP[dt]
+        assert orc.max_rel_err(f64(y), orc.rmsnorm(h64(x, dt), h64(g, dt), 1e-6)) <= tol
         # fused: x += delta (in place), y = norm(x)
-        y2 = torch.empty_like(xd)
+        y2 = iso.DeviceArray((T, H), dt)
         ctx.residual_rmsnorm(xd, dd, gd, y2, T, ctx.stream0)
         ctx.sync()
-        x1 = f64(x) + f64(delta)
+        x1 = h64(x, dt) + h64(delta, dt)
         assert orc.max_rel_err(f64(xd), x1) <= tol
-        assert orc.max_rel_err(f64(y2), orc.rmsnorm(x1, f64(g), 1e-6)) <= tol
+        assert orc.max_rel_err(f64(y2), orc.rmsnorm(x1, h64(g, dt), 1e-6)) <= tol
         # residual only
-        xd2 = x.to(DEV)
+        xd2 = dev(x, dt)
         ctx.residual_rmsnorm(xd2, dd, None, None, T, ctx.stream0)
         ctx.sync()
         assert orc.max_rel_err(f64(xd2), x1) <= tol
 
 
-@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("nq,nkv,d", [(4, 4, 64), (8, 1, 128), (13, 13, 128), (6, 2, 64)])
 def test_rope_kv_write(dt, nq, nkv, d):
     Tc, q_offset, max_seq = 70, 41, 128
-    torch.manual_seed(nq * 100 + d)
-    qkv = torch.randn(Tc, (nq + 2 * nkv) * d).to(dt)
+    qkv = iso_inputs.randn((Tc, (nq + 2 * nkv) * d), seed=nq * 100 + d, dtype=dt)
+    seven = iso_inputs.store(np.full((max_seq, nkv, d), 7.0, dtype=np.float32), dt)
     with make_ctx(256, nq, nkv, d, 64, dt, max_seq) as ctx:
-        qd = qkv.to(DEV)
-        kc = torch.full((max_seq, nkv, d), 7.0, dtype=dt, device=DEV)
-        vc = torch.full((max_seq, nkv, d), 7.0, dtype=dt, device=DEV)
+        qd, kc, vc = dev(qkv, dt), dev(seven, dt), dev(seven, dt)
         ctx.rope_kv_write(qd, kc, vc, Tc, q_offset, ctx.stream0)
         ctx.sync()
         pos = np.arange(q_offset, q_offset + Tc)
-        ref = f64(qkv)
+        ref = h64(qkv, dt)
         q_ref = orc.rope(ref[:, : nq * d].reshape(Tc, nq, d), pos, 10000.0)
         k_ref = orc.rope(ref[:, nq * d:(nq + nkv) * d].reshape(Tc, nkv, d), pos, 10000.0)
         v_ref = ref[:, (nq + nkv) * d:].reshape(Tc, nkv, d)
-        tol = TOL_STEP[dtype_name(dt)]
+        tol = TOL_STEP[dt]
+        kcn, vcn = f64(kc), f64(vc)
         assert orc.max_rel_err(f64(qd)[:, : nq * d].reshape(Tc, nq, d), q_ref) <= tol
-        assert orc.max_rel_err(f64(kc)[q_offset:q_offset + Tc], k_ref) <= tol
-        np.testing.assert_array_equal(f64(vc)[q_offset:q_offset + Tc], v_ref)       # v is a copy: bit-exact
+        assert orc.max_rel_err(kcn[q_offset:q_offset + Tc], k_ref) <= tol
+        np.testing.assert_array_equal(vcn[q_offset:q_offset + Tc], v_ref)       # v is a copy: bit-exact
         # rows outside the chunk are untouched
-        assert torch.all(kc[:q_offset] == 7.0) and torch.all(kc[q_offset + Tc:] == 7.0)
-        assert torch.all(vc[:q_offset] == 7.0) and torch.all(vc[q_offset + Tc:] == 7.0)
+        assert np.all(kcn[:q_offset] == 7.0) and np.all(kcn[q_offset + Tc:] == 7.0)
+        assert np.all(vcn[:q_offset] == 7.0) and np.all(vcn[q_offset + Tc:] == 7.0)
 
 
-@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("T,F", [(1, 8), (33, 688), (129, 3584)])
 def test_swiglu(dt, T, F):
-    torch.manual_seed(F)
-    gu = (2.0 * torch.randn(T, 2 * F)).to(dt)
+    gu = iso_inputs.randn((T, 2 * F), seed=F, dtype=dt, scale=2.0)
     with make_ctx(256, 4, 4, 64, F, dt, 256) as ctx:
-        a = torch.empty(T, F, dtype=dt, device=DEV)
-        ctx.swiglu(gu.to(DEV), a, T, ctx.stream0)
+        a = iso.DeviceArray((T, F), dt)
+        ctx.swiglu(dev(gu, dt), a, T, ctx.stream0)
         ctx.sync()
-        assert orc.max_rel_err(f64(a), orc.swiglu(f64(gu))) <= TOL_STEP[dtype_name(dt)]
+        assert orc.max_rel_err(f64(a), orc.swiglu(h64(gu, dt))) <= TOL_STEP[dt]
 
 
 # ------------------------------------------------------------------------------ projections
 
 GEMM_SHAPES = [(1, 8, 8), (64, 128, 64), (128, 128, 64), (129, 130, 72), (300, 257, 1000), (77, 768, 256),
-               (256, 384, 688), (513, 1280, 2048)]
+               (256, 384, 688), (513, 1280, 2048), (1000, 520, 1664), (260, 8, 64)]
 
 
-@pytest.mark.parametrize("dt,flags", [(torch.float32, 0), (torch.bfloat16, 0),
-                                      (torch.bfloat16, iso.ISO_FLAG_SIMPLE_GEMM)])
+@pytest.mark.parametrize("dt,flags", [("f32", 0), ("bf16", 0), ("bf16", iso.ISO_FLAG_GEMM_STAGED),
+                                      ("bf16", iso.ISO_FLAG_SIMPLE_GEMM),
+                                      ("bf16", 1 << 8), ("bf16", 2 << 8), ("bf16", 4 << 8), ("bf16", 5 << 8)])
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
 def test_gemm_rowpar(dt, flags, M, N, K):
-    torch.manual_seed(M + N + K)
-    a = torch.randn(M, K).to(dt)
-    w = (torch.randn(N, K) * K ** -0.5).to(dt)
+    a = iso_inputs.randn((M, K), seed=M + N + K, dtype=dt)
+    w = iso_inputs.randn((N, K), seed=M + N + K + 1, dtype=dt, scale=K ** -0.5)
     with make_ctx(256, 4, 4, 64, 64, dt, 256) as ctx:
         ctx.set_flags(flags)
-        c = torch.zeros(M, N, dtype=dt, device=DEV)
-        sink = torch.zeros(M, N, dtype=dt).pin_memory()
-        ctx.gemm_rowpar(a.to(DEV), w.to(DEV), c, M, N, K, ctx.stream0, sink.data_ptr())
+        c = iso.DeviceArray((M, N), dt, fill_byte=0)
+        sink = iso.PinnedArray((M, N), dt)
+        sink.array[...] = 0
+        ctx.gemm_rowpar(dev(a, dt), dev(w, dt), c, M, N, K, ctx.stream0, sink.ptr)
         ctx.sync()
-        ref = orc.linear(f64(a), f64(w))
-        assert orc.max_rel_err(f64(c), ref) <= TOL_STEP[dtype_name(dt)]
-        assert torch.equal(sink, c.cpu())          # the communication stand-in moved exactly the partial
+        ref = orc.linear(h64(a, dt), h64(w, dt))
+        assert orc.max_rel_err(f64(c), ref) <= TOL_STEP[dt]
+        np.testing.assert_array_equal(sink.array, c.numpy())   # the communication stand-in moved exactly the partial
+        sink.free()
 
 
 def test_gemm_rejects_bad_shapes():
-    with make_ctx(256, 4, 4, 64, 64, torch.bfloat16, 256) as ctx:
-        a = torch.zeros(4, 12, dtype=torch.bfloat16, device=DEV)
+    with make_ctx(256, 4, 4, 64, 64, "bf16", 256) as ctx:
+        a = iso.DeviceArray((4, 12), "bf16", fill_byte=0)
         for (M, N, K) in ((4, 4, 12), (0, 4, 8), (4, -1, 8)):
             with pytest.raises(iso.IsoError) as ei:
                 ctx.gemm_rowpar(a, a, a, M, N, K, ctx.stream0)
@@ -156,30 +157,30 @@ ATTN_CASES = [
 ]
 
 
-@pytest.mark.parametrize("dt,d,flags", [(torch.float32, 64, 0), (torch.float32, 128, 0), (torch.bfloat16, 128, 0),
-                                        (torch.bfloat16, 128, iso.ISO_FLAG_SIMPLE_ATTN), (torch.bfloat16, 64, 0)])
+@pytest.mark.parametrize("dt,d,flags", [("f32", 64, 0), ("f32", 128, 0), ("bf16", 128, 0),
+                                        ("bf16", 128, iso.ISO_FLAG_SIMPLE_ATTN), ("bf16", 64, 0)])
 @pytest.mark.parametrize("Tc,q_offset,kv_len,nq,nkv", ATTN_CASES)
 def test_attn_chunk(dt, d, flags, Tc, q_offset, kv_len, nq, nkv):
     q, k, v = iso_inputs.make_qkv_cache(Tc, kv_len, nq, nkv, d, seed=Tc + q_offset, dtype=dt)
     with make_ctx(256, nq, nkv, d, 64, dt, 1024) as ctx:
         ctx.set_flags(flags)
-        out = torch.zeros(Tc, nq * d, dtype=dt, device=DEV)
-        ctx.attn_chunk(q.to(DEV), k.to(DEV), v.to(DEV), out, Tc, q_offset, kv_len, ctx.stream0)
+        out = iso.DeviceArray((Tc, nq * d), dt, fill_byte=0)
+        ctx.attn_chunk(dev(q, dt), dev(k, dt), dev(v, dt), out, Tc, q_offset, kv_len, ctx.stream0)
         ctx.sync()
-        ref = orc.attention_chunk(f64(q), f64(k), f64(v), q_offset, kv_len).reshape(Tc, nq * d)
-        tol = TOL_STEP[dtype_name(dt)]
-        if dt == torch.bfloat16 and d == 128 and flags == 0:
+        ref = orc.attention_chunk(h64(q, dt), h64(k, dt), h64(v, dt), q_offset, kv_len).reshape(Tc, nq * d)
+        tol = TOL_STEP[dt]
+        if dt == "bf16" and d == 128 and flags == 0:
             # the matrix-core kernel rounds the probabilities to bf16 before the second product:
             # |d out| <= 2^-9 * sum_j p_j |v_j| <= 2^-9 max|v|, on top of the 2^-8 output rounding
             rms = float(np.sqrt(np.mean(ref * ref)))
-            tol = 2.0 ** -9 * float(v.abs().max()) / rms + 2.0 ** -8 + 1e-4
+            tol = 2.0 ** -9 * float(np.abs(h64(v, dt)).max()) / rms + 2.0 ** -8 + 1e-4
         err = orc.max_rel_err(f64(out), ref)
         assert err <= tol, (err, tol)
 
 
 def test_attn_chunk_rejects_bad_arguments():
-    with make_ctx(256, 4, 4, 64, 64, torch.float32, 64) as ctx:
-        t = torch.zeros(64, 256, device=DEV)
+    with make_ctx(256, 4, 4, 64, 64, "f32", 64) as ctx:
+        t = iso.DeviceArray((64, 256), "f32", fill_byte=0)
         for args, code in (((0, 0, 1), iso.ISO_ERR_SHAPE), ((4, -1, 4), iso.ISO_ERR_SHAPE), ((4, 0, 0), iso.ISO_ERR_SHAPE),
                            ((4, 0, 65), iso.ISO_ERR_WORKSPACE), ((65, 0, 4), iso.ISO_ERR_WORKSPACE)):
             with pytest.raises(iso.IsoError) as ei:
@@ -189,30 +190,32 @@ def test_attn_chunk_rejects_bad_arguments():
 
 # ------------------------------------------------------------------------------ whole layer
 
-def run_layer(ctx, w_dev, x_cpu, T, split, nkv, d, max_seq, comm=iso.ISO_COMM_NONE, sched=iso.ISO_SCHED_OVERLAP,
+def run_layer(ctx, w_dev, x_host, dt, T, split, nkv, d, max_seq, comm=iso.ISO_COMM_NONE, sched=iso.ISO_SCHED_OVERLAP,
               poison=False):
-    x = x_cpu.to(DEV).clone()
-    fill = float("nan") if poison else 0.0
-    kc = torch.full((max_seq, nkv, d), fill, dtype=x.dtype, device=DEV)
-    vc = torch.full((max_seq, nkv, d), fill, dtype=x.dtype, device=DEV)
-    torch.cuda.synchronize()
+    x = dev(x_host, dt)
+    kc = iso.DeviceArray((max_seq, nkv, d), dt, fill_byte=NAN_BYTE if poison else 0)
+    vc = iso.DeviceArray((max_seq, nkv, d), dt, fill_byte=NAN_BYTE if poison else 0)
     ctx.layer_prefill(w_dev, x, kc, vc, T, split, comm, sched)
     ctx.sync()
     return x, kc, vc
+
+
+def oracle_weights(w, dt):
+    return {k: h64(v, dt) for k, v in w.items()}
 
 
 def test_tiny_f32_layer_unsplit_and_every_tested_split():
     wl = iso_inputs.WORKLOADS["tiny_f32"]
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
     sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
-    ref = orc.layer_unsplit(f64(x), {k: f64(v) for k, v in w.items()}, sh)
-    w_dev = {k: v.to(DEV) for k, v in w.items()}
-    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, torch.float32, wl.seq) as ctx:
+    ref = orc.layer_unsplit(h64(x, "f32"), oracle_weights(w, "f32"), sh)
+    w_dev = iso.upload_weights(w, "f32")
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, "f32", wl.seq) as ctx:
         for split in (0, wl.seq, 64, 1, 127, 33, 77, 100):
             for sched in (iso.ISO_SCHED_OVERLAP, iso.ISO_SCHED_SERIAL):
                 for comm in (iso.ISO_COMM_NONE, iso.ISO_COMM_D2H):
-                    out, kc, vc = run_layer(ctx, w_dev, x, wl.seq, split, wl.n_kv_heads, wl.head_dim, wl.seq, comm,
-                                            sched, poison=True)
+                    out, kc, vc = run_layer(ctx, w_dev, x, "f32", wl.seq, split, wl.n_kv_heads, wl.head_dim, wl.seq,
+                                            comm, sched, poison=True)
                     err = orc.max_rel_err(f64(out), ref["x_out"])
                     assert err <= TOL_LAYER["f32"], (split, sched, comm, err)
                     assert orc.max_rel_err(f64(kc), ref["k_cache"]) <= TOL_STEP["f32"]
@@ -223,29 +226,47 @@ def test_tiny_f32_layer_matches_the_oracles_iso_path_too():
     wl = iso_inputs.WORKLOADS["tiny_f32"]
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
     sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
-    ref = orc.layer_iso(f64(x), {k: f64(v) for k, v in w.items()}, sh, wl.split)
-    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, torch.float32, wl.seq) as ctx:
-        out, _, _ = run_layer(ctx, {k: v.to(DEV) for k, v in w.items()}, x, wl.seq, wl.split, wl.n_kv_heads,
+    ref = orc.layer_iso(h64(x, "f32"), oracle_weights(w, "f32"), sh, wl.split)
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, "f32", wl.seq) as ctx:
+        out, _, _ = run_layer(ctx, iso.upload_weights(w, "f32"), x, "f32", wl.seq, wl.split, wl.n_kv_heads,
                               wl.head_dim, wl.seq)
         assert orc.max_rel_err(f64(out), ref["x_out"]) <= TOL_LAYER["f32"]
 
 
-@pytest.mark.parametrize("flags", [0, iso.ISO_FLAG_SIMPLE_GEMM | iso.ISO_FLAG_SIMPLE_ATTN])
+def test_comm_stand_in_delivers_both_partials_to_the_host():
+    """With ISO_COMM_D2H the pinned sink holds the o_proj partial and the down partial of every token: check
+    them against the oracle's intermediates (x1 - x and x_out - x1)."""
+    wl = iso_inputs.WORKLOADS["tiny_f32"]
+    x, w = iso_inputs.make_workload_inputs(wl, seed=0)
+    sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
+    ref = orc.layer_unsplit(h64(x, "f32"), oracle_weights(w, "f32"), sh)
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, "f32", wl.seq) as ctx:
+        run_layer(ctx, iso.upload_weights(w, "f32"), x, "f32", wl.seq, wl.split, wl.n_kv_heads, wl.head_dim, wl.seq,
+                  iso.ISO_COMM_D2H)
+        import ctypes
+        n = wl.seq * wl.hidden
+        sink = np.frombuffer((ctypes.c_float * (2 * n)).from_address(ctx.host_sink()), dtype=np.float32).copy()
+        pa, pm = sink[:n].reshape(wl.seq, wl.hidden), sink[n:].reshape(wl.seq, wl.hidden)
+        assert orc.max_rel_err(pa, ref["x1"] - h64(x, "f32")) <= TOL_LAYER["f32"]
+        assert orc.max_rel_err(pm, ref["x_out"] - ref["x1"]) <= TOL_LAYER["f32"]
+
+
+@pytest.mark.parametrize("flags", [0, iso.ISO_FLAG_SIMPLE_GEMM | iso.ISO_FLAG_SIMPLE_ATTN, iso.ISO_FLAG_GEMM_STAGED,
+                                   iso.ISO_FLAG_NO_FUSE, 1 << 8, 2 << 8, 3 << 8, 4 << 8])
 @pytest.mark.parametrize("hidden,nq,nkv,ffn,T,splits", [
     (512, 4, 1, 768, 300, (0, 130, 299)),       # GQA, ragged everything
     (384, 3, 3, 200, 257, (128, 1)),            # MHA, odd head count
 ])
 def test_small_bf16_layer_all_rows(flags, hidden, nq, nkv, ffn, T, splits):
-    d = 128
-    dt = torch.bfloat16
+    d, dt = 128, "bf16"
     w = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=11, dtype=dt)
     x = iso_inputs.make_hidden(T, hidden, seed=11, dtype=dt)
-    ref = orc.layer_unsplit(f64(x), {k: f64(v) for k, v in w.items()}, shape_of(hidden, nq, nkv, d, ffn))
-    w_dev = {k: v.to(DEV) for k, v in w.items()}
+    ref = orc.layer_unsplit(h64(x, dt), oracle_weights(w, dt), shape_of(hidden, nq, nkv, d, ffn))
+    w_dev = iso.upload_weights(w, dt)
     with make_ctx(hidden, nq, nkv, d, ffn, dt, 320) as ctx:
         ctx.set_flags(flags)
         for split in splits:
-            out, kc, vc = run_layer(ctx, w_dev, x, T, split, nkv, d, 320, iso.ISO_COMM_D2H, poison=True)
+            out, kc, vc = run_layer(ctx, w_dev, x, dt, T, split, nkv, d, 320, iso.ISO_COMM_D2H, poison=True)
             err = orc.max_rel_err(f64(out), ref["x_out"])
             assert err <= TOL_LAYER["bf16"], (split, err)
             # cached K went through three bf16 roundings (norm output, projection output, rotation)
@@ -254,22 +275,20 @@ def test_small_bf16_layer_all_rows(flags, hidden, nq, nkv, ffn, T, splits):
 
 
 def test_two_layer_stack_equals_two_oracle_layers():
-    hidden, nq, nkv, d, ffn, T, split = 256, 2, 1, 128, 256, 200, 90
-    dt = torch.bfloat16
+    hidden, nq, nkv, d, ffn, T, split, dt = 256, 2, 1, 128, 256, 200, 90, "bf16"
     layers = [iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=20 + l, dtype=dt) for l in range(2)]
     x = iso_inputs.make_hidden(T, hidden, seed=5, dtype=dt)
     sh = shape_of(hidden, nq, nkv, d, ffn)
-    ref = f64(x)
+    ref = h64(x, dt)
     for w in layers:
-        ref = orc.layer_unsplit(ref, {k: f64(v) for k, v in w.items()}, sh)["x_out"]
+        ref = orc.layer_unsplit(ref, oracle_weights(w, dt), sh)["x_out"]
+    layers_dev = [iso.upload_weights(w, dt) for w in layers]
     with make_ctx(hidden, nq, nkv, d, ffn, dt, T) as ctx:
         for s in (0, split):
-            xd = x.to(DEV).clone()
-            kcs = torch.zeros(2, T, nkv, d, dtype=dt, device=DEV)
-            vcs = torch.zeros(2, T, nkv, d, dtype=dt, device=DEV)
-            torch.cuda.synchronize()
-            ctx.stack_prefill([{k: v.to(DEV) for k, v in w.items()} for w in layers], xd, kcs, vcs, T, s,
-                              iso.ISO_COMM_D2H)
+            xd = dev(x, dt)
+            kcs = iso.DeviceArray((2, T, nkv, d), dt, fill_byte=NAN_BYTE)
+            vcs = iso.DeviceArray((2, T, nkv, d), dt, fill_byte=NAN_BYTE)
+            ctx.stack_prefill(layers_dev, xd, kcs, vcs, T, s, iso.ISO_COMM_D2H)
             ctx.sync()
             # two layers compound the per-layer bf16 error: allow twice the per-layer bound
             assert orc.max_rel_err(f64(xd), ref) <= 2 * TOL_LAYER["bf16"]
@@ -278,34 +297,35 @@ def test_two_layer_stack_equals_two_oracle_layers():
 def test_kv_event_orders_the_chunks_and_runs_are_bit_identical():
     """Chunk 1 must not read the cache before chunk 0 wrote it (Section 3.1).  The cache starts as NaN, so a
     read that overtook the write would surface as NaN; repeated runs must also agree bit for bit."""
-    hidden, nq, nkv, d, ffn, T, split = 1024, 8, 1, 128, 1024, 1024, 512
-    dt = torch.bfloat16
-    w = {k: v.to(DEV) for k, v in iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=3, dtype=dt).items()}
+    hidden, nq, nkv, d, ffn, T, split, dt = 1024, 8, 1, 128, 1024, 1024, 512, "bf16"
+    w = iso.upload_weights(iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=3, dtype=dt), dt)
     x = iso_inputs.make_hidden(T, hidden, seed=3, dtype=dt)
     with make_ctx(hidden, nq, nkv, d, ffn, dt, T) as ctx:
         first = None
         for _ in range(10):
-            out, _, _ = run_layer(ctx, w, x, T, split, nkv, d, T, iso.ISO_COMM_D2H, poison=True)
-            assert not torch.isnan(out).any()
+            out, _, _ = run_layer(ctx, w, x, dt, T, split, nkv, d, T, iso.ISO_COMM_D2H, poison=True)
+            bits = out.numpy()
+            assert not np.isnan(iso_inputs.bf16_bits_to_f32(bits)).any()
             if first is None:
-                first = out.clone()
-            assert torch.equal(out, first)
+                first = bits
+            np.testing.assert_array_equal(bits, first)
 
 
 def test_layer_prefill_rejects_bad_arguments():
-    with make_ctx(256, 4, 4, 64, 688, torch.float32, 128) as ctx:
+    with make_ctx(256, 4, 4, 64, 688, "f32", 128) as ctx:
         wl = iso_inputs.WORKLOADS["tiny_f32"]
         x, w = iso_inputs.make_workload_inputs(wl, seed=0)
-        w_dev = {k: v.to(DEV) for k, v in w.items()}
-        xd = x.to(DEV)
-        kc = torch.zeros(128, 4, 64, device=DEV)
+        w_dev = iso.upload_weights(w, "f32")
+        xd = dev(x, "f32")
+        kc = iso.DeviceArray((128, 4, 64), "f32", fill_byte=0)
+        vc = iso.DeviceArray((128, 4, 64), "f32", fill_byte=0)
         for T, split, code in ((129, 0, iso.ISO_ERR_WORKSPACE), (128, 129, iso.ISO_ERR_SPLIT), (128, -1, iso.ISO_ERR_SPLIT),
                                (0, 0, iso.ISO_ERR_SHAPE)):
             with pytest.raises(iso.IsoError) as ei:
-                ctx.layer_prefill(w_dev, xd, kc, kc.clone(), T, split)
+                ctx.layer_prefill(w_dev, xd, kc, vc, T, split)
             assert ei.value.code == code
         with pytest.raises(iso.IsoError) as ei:
-            ctx.layer_prefill(w_dev, xd, kc, kc, 128, 64, comm=5)
+            ctx.layer_prefill(w_dev, xd, kc, vc, 128, 64, comm=5)
         assert ei.value.code == iso.ISO_ERR_SHAPE
 
 
@@ -313,21 +333,22 @@ def test_layer_prefill_rejects_bad_arguments():
 
 def _sampled_parity(name, split, n_rows=64):
     wl = iso_inputs.WORKLOADS[name]
+    dt = wl.dtype
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
     rows = iso_inputs.sample_rows(wl.seq, split, n_rows, seed=0)
     sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
-    ref = orc.layer_rows(f64(x), {k: f64(v) for k, v in w.items()}, sh, rows)
-    w_dev = {k: v.to(DEV) for k, v in w.items()}
+    ref = orc.layer_rows(h64(x, dt), oracle_weights(w, dt), sh, rows)
+    w_dev = iso.upload_weights(w, dt)
     errs = {}
-    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.torch_dtype, wl.seq) as ctx:
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, wl.seq) as ctx:
         for s in (0, split):
-            out, kc, vc = run_layer(ctx, w_dev, x, wl.seq, s, wl.n_kv_heads, wl.head_dim, wl.seq, iso.ISO_COMM_D2H,
+            out, kc, vc = run_layer(ctx, w_dev, x, dt, wl.seq, s, wl.n_kv_heads, wl.head_dim, wl.seq, iso.ISO_COMM_D2H,
                                     poison=True)
-            errs[s] = orc.max_rel_err(f64(out[rows]), ref["x_out"])
-            assert errs[s] <= TOL_LAYER[wl.dtype], (name, s, errs[s])
+            errs[s] = orc.max_rel_err(f64(out)[rows], ref["x_out"])
+            assert errs[s] <= TOL_LAYER[dt], (name, s, errs[s])
             ek = orc.max_rel_err(f64(kc), ref["k_cache"])
             ev = orc.max_rel_err(f64(vc), ref["v_cache"])
-            assert ek <= TOL_LAYER[wl.dtype] and ev <= TOL_LAYER[wl.dtype], (name, s, ek, ev)
+            assert ek <= TOL_LAYER[dt] and ev <= TOL_LAYER[dt], (name, s, ek, ev)
             errs[(s, "kv")] = (ek, ev)
     print(name, "max_rel_err", errs)
 

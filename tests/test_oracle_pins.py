@@ -207,15 +207,15 @@ def test_gqa_head_mapping_is_contiguous_groups():
 
 # ------------------------------------------------------------------ whole layer
 
-def _np_weights(w):
-    return {k: v.to(dtype=__import__("torch").float64).numpy() for k, v in w.items()}
+def _np_weights(w, dtype="f32"):
+    return {k: iso_inputs.to_f64(v, dtype) for k, v in w.items()}
 
 
 def _tiny():
     wl = iso_inputs.WORKLOADS["tiny_f32"]
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
     sh = orc.LayerShape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.rms_eps, wl.rope_base)
-    return wl, x.double().numpy(), _np_weights(w), sh
+    return wl, iso_inputs.to_f64(x, wl.dtype), _np_weights(w, wl.dtype), sh
 
 
 def test_two_token_layer_closed_form():
@@ -292,10 +292,9 @@ def scalar_layer(x, w, sh):
 
 @pytest.mark.parametrize("nq,nkv", [(2, 1), (2, 2), (4, 2)])
 def test_layer_equals_scalar_brute_force_on_tiny_shapes(nq, nkv):
-    import torch
     sh = orc.LayerShape(hidden=6, n_q_heads=nq, n_kv_heads=nkv, head_dim=4, ffn=5, rms_eps=1e-6, rope_base=10000.0)
-    w = _np_weights(iso_inputs.make_layer(6, nq, nkv, 4, 5, seed=3, dtype=torch.float32))
-    x = iso_inputs.make_hidden(5, 6, seed=3, dtype=torch.float32).double().numpy()
+    w = _np_weights(iso_inputs.make_layer(6, nq, nkv, 4, 5, seed=3, dtype="f32"))
+    x = iso_inputs.to_f64(iso_inputs.make_hidden(5, 6, seed=3, dtype="f32"), "f32")
     want = scalar_layer(x.tolist(), {k: v.tolist() for k, v in w.items()}, sh)
     np.testing.assert_allclose(orc.layer_unsplit(x, w, sh)["x_out"], want, rtol=1e-12, atol=1e-13)
     for s in range(1, 5):
@@ -377,3 +376,15 @@ def test_error_metric():
     rms = math.sqrt(21.0 / 4.0)
     assert orc.max_rel_err(got, ref) == pytest.approx(max(0.02 / rms, 0.01 / rms, 0.02 / 2.0 if 2.0 > rms else 0.0))
     assert orc.max_rel_err(ref, ref) == 0.0
+
+
+def test_bf16_storage_round_trip_is_round_to_nearest_even():
+    """The input recipe's bf16 cast: exact halves go to the even neighbour, values survive a round trip."""
+    a = np.array([1.0, 1.00390625, 1.01171875, -3.14159, 65504.0, 0.0], dtype=np.float32)
+    bits = iso_inputs.f32_to_bf16_bits(a)
+    back = iso_inputs.bf16_bits_to_f32(bits)
+    # 1 + 2^-8 lies exactly between 1 and 1 + 2^-7: ties go to the even mantissa (1.0);
+    # 1 + 3*2^-8 lies between 1 + 2^-7 (odd) and 1 + 2^-6 (even): goes up
+    np.testing.assert_array_equal(back[:3], [1.0, 1.0, 1.015625])
+    assert abs(back[3] + 3.14159) <= 2.0 ** -7 and back[4] == 65536.0 and back[5] == 0.0
+    np.testing.assert_array_equal(iso_inputs.f32_to_bf16_bits(back), bits)
