@@ -26,7 +26,7 @@ ISO_ERR_NULL, ISO_ERR_SHAPE, ISO_ERR_DTYPE, ISO_ERR_SPLIT, ISO_ERR_WORKSPACE, IS
 ISO_F32, ISO_BF16 = 0, 1
 ISO_COMM_NONE, ISO_COMM_D2H = 0, 1
 ISO_SCHED_OVERLAP, ISO_SCHED_SERIAL = 0, 1
-ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN, ISO_FLAG_GEMM_STAGED, ISO_FLAG_NO_FUSE = 1, 2, 4, 8
+ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN, ISO_FLAG_GEMM_STAGED, ISO_FLAG_NO_FUSE, ISO_FLAG_ATTN_STAGED = 1, 2, 4, 8, 16
 
 EXPORTS = [
     "iso_validate_cfg", "iso_plan_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",

@@ -1,0 +1,245 @@
+// Chunk attention over the KV cache on the gfx950 matrix cores, pipelined variant (bf16, head_dim 128).
+// Local query row i of the chunk is token q_offset + i and sees keys j <= q_offset + i, j < kv_len
+// (paper Section 3.1: the second chunk reads the cache the first chunk wrote, plus its own causal block).
+//
+// Same mathematics and register layout as the staged kernel (scores transposed, S^T = K Q^T, so that the
+// softmax statistics are per-lane scalars and the probabilities feed the second product O^T = V^T P^T
+// straight from registers).  What differs is how K and V reach the matrix cores:
+//   * K and V tiles (64 keys x 128 dims) go global -> LDS directly (buffer_load ... lds) into two stages;
+//     the loads of tile j+1 are in flight while tile j is multiplied; one barrier per tile.  Rows past
+//     kv_len are out of the buffer's range and read as zero.
+//   * Both tiles keep their natural row-major layout; the 16-byte chunks of a row are XOR-swizzled on the
+//     global side (the LDS slot of a lane's 16 bytes is fixed by the lane number) so that the operand reads
+//     are free of bank conflicts.
+//   * V is read with ds_read_b64_tr_b16: 16 lanes fetch a 4-key x 16-dim block and receive it transposed,
+//     i.e. each lane gets 4 consecutive keys of one dim -- the k-contiguous operand layout the MFMA wants
+//     for V^T -- with no transposing pass over V anywhere.
+#include "iso_internal.h"
+
+namespace {
+
+constexpr int D = 128;
+constexpr int BM = 128;            // query rows per workgroup (4 waves x 32)
+constexpr int BN = 64;             // keys per tile
+constexpr int ROW_B = D * 2;       // bytes per K/V row in LDS
+constexpr int TILE_B = BN * ROW_B; // 16 KB
+constexpr int STAGE_B = 2 * TILE_B;
+
+typedef __bf16 bf16x4_v __attribute__((ext_vector_type(4)));
+
+// NSTAGE LDS stages: tile j + NSTAGE - 1 is requested while tile j is multiplied.  Two stages (64 KB) let two
+// workgroups share a compute unit and hide each other's latency; four stages (128 KB) are for launches too
+// small to fill the chip twice over, where the only thing hiding the load latency is the prefetch distance.
+template <int NSTAGE>
+__global__ __launch_bounds__(256) void attn_bf16_dtl_kernel(const bf16_t *__restrict__ Q,
+                                                            const bf16_t *__restrict__ Kc,
+                                                            const bf16_t *__restrict__ Vc,
+                                                            bf16_t *__restrict__ Out, int Tc, int q_offset,
+                                                            int kv_len, int nq, int nkv, int q_stride) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lcol = lane & 31, lgrp = lane >> 5;
+    const int n_tiles_m = (Tc + BM - 1) / BM;
+    const int tile_m = n_tiles_m - 1 - blockIdx.x;      // longest rows first
+    const int h = blockIdx.y;
+    const int g = h / (nq / nkv);
+    const int m0 = tile_m * BM;
+
+    // ---- this wave's 32 query rows as the B operand (k = head dim): 8 k-steps of 16
+    const int q_row = min(m0 + wave * 32 + lcol, Tc - 1);
+    const int q_abs = q_offset + m0 + wave * 32 + lcol;
+    const int wave_q_max = q_offset + m0 + wave * 32 + 31;
+    bf16x8_t qf[D / 16];
+    {
+        const bf16_t *qp = Q + (size_t)q_row * q_stride + (size_t)h * D + lgrp * 8;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t *>(qp + ks * 16);
+    }
+
+    // ---- direct-to-LDS loads: wave-load = 4 rows x 256 B; lane = (row l/16, slot l%16)
+    const uint32_t row_stride = (uint32_t)nkv * D * 2u;                         // bytes between cache rows
+    const uint32_t n_rec = (uint32_t)(kv_len - 1) * row_stride + (uint32_t)ROW_B;  // this head's slice, rows < kv_len
+    const __amdgpu_buffer_rsrc_t rs_k =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(Kc + (size_t)g * D), 0, (int)n_rec, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_v =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(Vc + (size_t)g * D), 0, (int)n_rec, 0x00020000);
+    uint32_t k_off[4], v_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = (wave + 4 * i) * 4 + (lane >> 4);
+        const int slot = lane & 15;
+        k_off[i] = (uint32_t)r * row_stride + (uint32_t)((slot ^ (r & 15)) << 4);
+        v_off[i] = (uint32_t)r * row_stride + (uint32_t)((slot ^ ((r & 3) << 2)) << 4);
+    }
+    auto issue = [&](int stage, int j0) {
+        unsigned char *base = lds + stage * STAGE_B;
+        const uint32_t tile_off = (uint32_t)j0 * row_stride;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_k, (__attribute__((address_space(3))) void *)(base + (wave + 4 * i) * 1024), 16, k_off[i] + tile_off, 0,
+                0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_v, (__attribute__((address_space(3))) void *)(base + TILE_B + (wave + 4 * i) * 1024), 16,
+                v_off[i] + tile_off, 0, 0, 0);
+    };
+
+    // ---- LDS read addressing
+    // K (A operand of S^T): lane = key row lcol of the 32-key block, 16-byte chunk 2*ks + lgrp, swizzled by row & 15
+    const int k_row_off = lcol * ROW_B;
+    const int k_sw = lcol & 15;
+    // V (A operand of O^T, transposing read): 16-lane group = 4 keys x 16 dims
+    const int s16 = lane & 15, half16 = (lane >> 4) & 1;
+    const int v_row_base = 4 * lgrp + (s16 >> 2);                 // + 32 sub + 16 t + 8 h
+    const int v_sw = ((s16 >> 2) & 3) << 2;
+    const int v_chunk_base = 2 * half16 + ((s16 & 3) >> 1);       // + 4 dt
+    const int v_byte = (s16 & 1) << 3;
+
+    f32x16_t o[D / 32];
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+    float m_run = -1e30f;
+    float l_run = 0.f;
+    const float sc = 1.4426950408889634f / sqrtf((float)D);
+
+    const int kv_end = min(kv_len, q_offset + min(m0 + BM, Tc));    // exclusive
+    const int n_tiles = (kv_end + BN - 1) / BN;
+
+#pragma unroll
+    for (int p = 0; p < NSTAGE - 1; ++p)
+        if (p < n_tiles) issue(p, p * BN);
+    for (int jt = 0; jt < n_tiles; ++jt) {
+        const int j0 = jt * BN;
+        // this wave's loads of tile jt have landed: in steady state the NSTAGE-2 younger tiles (8 loads each)
+        // may still be in flight; near the end fewer are outstanding, so wait for everything
+        if (NSTAGE > 2 && jt + NSTAGE - 2 < n_tiles)
+            __builtin_amdgcn_s_waitcnt(0x0F70 | ((8 * (NSTAGE - 2)) & 15) | (((8 * (NSTAGE - 2)) >> 4) << 14));
+        else
+            __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();                    // ... everyone's have, and tile jt-1 is no longer being read
+        if (jt + NSTAGE - 1 < n_tiles) issue((jt + NSTAGE - 1) % NSTAGE, j0 + (NSTAGE - 1) * BN);
+        if (j0 > wave_q_max) continue;      // every key of this tile is above this wave's diagonal
+        const unsigned char *kb = lds + (jt % NSTAGE) * STAGE_B;
+        const unsigned char *vb = kb + TILE_B;
+
+        // --- S^T = K Q^T for two 32-key blocks
+        f32x16_t s[2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) {
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(kb + sub * 32 * ROW_B + k_row_off +
+                                                                         (((2 * ks + lgrp) ^ k_sw) << 4));
+                s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[sub], 0, 0, 0);
+            }
+        }
+        // --- mask (only tiles that touch the diagonal or the end of the cache), scale to log2 domain
+        const bool need_mask = (j0 + BN - 1 > q_offset + m0 + wave * 32) || (j0 + BN > kv_len);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float v = s[sub][r] * sc;
+                if (need_mask) {
+                    const int key = j0 + sub * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4);
+                    if (key > q_abs || key >= kv_len) v = -INFINITY;
+                }
+                s[sub][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8_t pb[2][2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(s[sub][r] - m_new);
+                psum += p;
+                pb[sub][r / 8][r % 8] = (bf16_t)p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        // --- O^T += V^T P^T.  k-slots 8*lgrp .. +8 of MFMA step (sub, t) hold keys
+        //     32 sub + 16 t + 4 lgrp + {0..3} and 32 sub + 16 t + 8 + 4 lgrp + {0..3}: two transposing reads.
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) {
+            const int cb = (((4 * dt + v_chunk_base) ^ v_sw) << 4) + v_byte;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int row = sub * 32 + t * 16 + v_row_base;
+                    const bf16x4_v lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (bf16x4_v __attribute__((address_space(3))) *)(vb + row * ROW_B + cb));
+                    const bf16x4_v hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (bf16x4_v __attribute__((address_space(3))) *)(vb + (row + 8) * ROW_B + cb));
+                    const bf16x8_t vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sub][t], o[dt], 0, 0, 0);
+                }
+        }
+    }
+
+    // --- normalise and store: lane holds column q = lcol, rows d = 32 dt + 8 (r/4) + 4 lgrp + r%4
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    const int row = m0 + wave * 32 + lcol;
+    if (row < Tc) {
+        bf16_t *op = Out + ((size_t)row * nq + h) * D;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                bf16x4_t v = {(bf16_t)(o[dt][r4 * 4 + 0] * inv), (bf16_t)(o[dt][r4 * 4 + 1] * inv),
+                              (bf16_t)(o[dt][r4 * 4 + 2] * inv), (bf16_t)(o[dt][r4 * 4 + 3] * inv)};
+                *reinterpret_cast<bf16x4_t *>(op + dt * 32 + 8 * r4 + 4 * lgrp) = v;
+            }
+    }
+#endif
+}
+
+}  // namespace
+
+bool iso_attn_bf16_dtl_supported(int d, int kv_len, int nkv) {
+    // the K/V slice of one head must be addressable with 32-bit byte offsets
+    return d == D && (long long)kv_len * nkv * D * 2 < (1ll << 31);
+}
+
+hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v, void *out, int Tc, int q_offset,
+                                    int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s) {
+    if (d != D) return hipErrorInvalidValue;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_dtl_kernel<2>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE_B);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_dtl_kernel<4>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 4 * STAGE_B);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((Tc + BM - 1) / BM, nq), block(256);
+    const bool small = (long long)grid.x * grid.y < 512;    // cannot put two workgroups on every compute unit
+    if (small)
+        hipLaunchKernelGGL(attn_bf16_dtl_kernel<4>, grid, block, 4 * STAGE_B, s, (const bf16_t *)q, (const bf16_t *)k,
+                           (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride);
+    else
+        hipLaunchKernelGGL(attn_bf16_dtl_kernel<2>, grid, block, 2 * STAGE_B, s, (const bf16_t *)q, (const bf16_t *)k,
+                           (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride);
+    return hipGetLastError();
+}

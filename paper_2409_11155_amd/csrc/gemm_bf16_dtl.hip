@@ -267,19 +267,13 @@ bool iso_gemm_bf16_dtl_supported(int M, int N, int K) {
            (long long)N * K < (1ll << 31);
 }
 
-// Tile shape: fewest "rounds" over the 256 compute units, larger tiles preferred on ties.
+// Tile shape.  Measured on MI355X over the projection shapes of the 30B/70B shards: the 256x256 tile wins as
+// soon as it yields at least ~128 workgroups (half the compute units: the chip is power-limited, so fewer busy
+// units clock higher and a half-filled launch of big tiles still beats a full launch of small ones); below that
+// the 128x128 tile (two workgroups per compute unit) is best.
 static int pick_variant(int M, int N) {
-    const int cand[4][3] = {{256, 256, 1}, {256, 128, 2}, {128, 256, 4}, {128, 128, 3}};
-    const double eff[4] = {1.0, 0.92, 0.92, 0.8};
-    double best = 1e300;
-    int v = 1;
-    for (int i = 0; i < 4; ++i) {
-        const long long tiles = (long long)((M + cand[i][0] - 1) / cand[i][0]) * ((N + cand[i][1] - 1) / cand[i][1]);
-        const long long rounds = (tiles + 255) / 256;
-        const double cost = (double)rounds * cand[i][0] * cand[i][1] / eff[i];
-        if (cost < best) { best = cost; v = cand[i][2]; }
-    }
-    return v;
+    const long long tiles_256 = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    return tiles_256 >= 128 ? 1 : 3;
 }
 
 // variant: 0 = pick by shape; 1 = 256x256 8 waves, 2 = 256x128 8 waves, 3 = 128x128 4 waves, 4 = 128x256 8 waves,
