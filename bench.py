@@ -135,26 +135,34 @@ def main() -> int:
     bf16 = wl.dtype == "bf16"
     peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
 
-    def gemm_roofline(kd):
-        ms = sum(kd[n][0] for n in gemm_names)
-        launches = sum(kd[n][1] for n in gemm_names)
-        flops = sum(gemm_flops_tok.values()) * T
-        return flops / (ms * 1e-3) / 1e12, ms / launches, flops / launches
-
-    ach, avg_ms, flops_per_launch = gemm_roofline(k_iso)
-    ach_alone, avg_ms_alone, _ = gemm_roofline(k_alone)
+    # ---- roofline of the dominant kernel: the gate/up projection (SwiGLU in its epilogue for bf16) -------
+    # one launch per chunk; algorithmic work of a launch = 2 * Tc * 2F * H flops, averaged over the chunks
+    dom = "gemm_gate_up"
+    dom_ms, dom_n = k_iso[dom]
+    dom_ms_alone, _ = k_alone[dom]
+    flops_per_launch = gemm_flops_tok[dom] * T / dom_n
+    ach = flops_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
+    ach_alone = flops_per_launch / (dom_ms_alone / dom_n * 1e-3) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
         try:
             with open(tpath) as f:
-                traffic = json.load(f).get(args.workload, {}).get("gemm_bytes_per_launch")
+                traffic = json.load(f).get(args.workload, {}).get("gate_up_bytes_per_launch")
         except Exception:
             traffic = None
-    roofline = {"bound": "mfma" if bf16 else "alu", "kernel": "gemm_bf16_mfma_kernel" if bf16 else "gemm_simple_kernel",
+    roofline = {"bound": "mfma" if bf16 else "alu",
+                "kernel": ("gemm_bf16_dtl_kernel<.., SWIGLU=true> (gate/up projection + SwiGLU)" if bf16
+                           else "gemm_simple_kernel<float> (gate/up projection)"),
                 "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
-                "avg_launch_ms": avg_ms, "flops_per_launch": flops_per_launch,
-                "achieved_alone": ach_alone, "frac_alone": ach_alone / peak, "avg_launch_ms_alone": avg_ms_alone}
+                "avg_launch_ms": dom_ms / dom_n, "flops_per_launch": flops_per_launch,
+                "launch_shape": {"M": T // dom_n, "N": 2 * F, "K": H, "launches_per_step": dom_n},
+                "measured": "HIP events around each launch, in its own stream, during ISO-scheduled steps",
+                "achieved_alone": ach_alone, "frac_alone": ach_alone / peak,
+                "avg_launch_ms_alone": dom_ms_alone / dom_n,
+                "all_gemms_tflops_alone": sum(gemm_flops_tok.values()) * T /
+                                          (sum(k_alone[n][0] for n in gemm_names) * 1e-3) / 1e12,
+                "attention_tflops_alone": pk_alone.get("attn", {}).get("tflops")}
 
     sum_x = k_comm["comm"][0]                                   # all copies of a step, back to back
     sum_c = t_serial - sum_x if t_serial > sum_x else sum(v[0] for k, v in k_alone.items() if k != "comm")
