@@ -32,6 +32,10 @@ def parse_args():
     ap.add_argument("--workload", default="30b_tp4_2k")
     ap.add_argument("--split", type=int, default=-1, help="split point (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="layers of a stack workload (default: the workload's)")
+    ap.add_argument("--distinct-layers", type=int, default=4,
+                    help="a stack draws this many distinct weight sets on the host and gives every layer its own "
+                         "device copy of one of them (layer l uses set l %% D)")
     return ap.parse_args()
 
 
@@ -52,19 +56,28 @@ def main() -> int:
     T = wl.seq
     dt = wl.dtype
     split = wl.split if args.split < 0 else args.split
+    L = args.layers if args.layers > 0 else wl.n_layers
     x_cpu, w_cpu = iso_inputs.make_workload_inputs(wl, seed=0)
-    w = iso.upload_weights(w_cpu, dt)
+    if L == 1:
+        layers = [iso.upload_weights(w_cpu, dt)]
+    else:   # every layer owns its device buffers; the host draws only a few distinct sets (see --distinct-layers)
+        host_sets = [w_cpu] + [iso_inputs.make_workload_inputs(wl, seed=0, layer=l)[1]
+                               for l in range(1, min(L, max(1, args.distinct_layers)))]
+        layers = [iso.upload_weights(host_sets[l % len(host_sets)], dt) for l in range(L)]
     x0 = iso.DeviceArray.from_numpy(x_cpu, dt)
     x = x0.clone()
-    kc = iso.DeviceArray((T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=0)
-    vc = iso.DeviceArray((T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=0)
+    kc = iso.DeviceArray((L, T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=0)
+    vc = iso.DeviceArray((L, T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=0)
     cfg = iso.make_cfg(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, T)
     ctx = iso.Context(cfg)
     K, W = args.steps, args.warmup
 
     def run(n, sp, comm, sched):
         for _ in range(n):
-            ctx.layer_prefill(w, x, kc, vc, T, sp, comm, sched)
+            if L == 1:
+                ctx.layer_prefill(layers[0], x, kc, vc, T, sp, comm, sched)
+            else:
+                ctx.stack_prefill(layers, x, kc, vc, T, sp, comm, sched)
 
     def timed(sp, comm, sched):
         """W warm-up steps, then exactly K steps between two full synchronisations; ms per step."""
@@ -103,14 +116,14 @@ def main() -> int:
     k_comm = kinds(split, D2H, SER, ksteps)
 
     H, F, d, nq = wl.hidden, wl.ffn, wl.head_dim, wl.n_q_heads
-    gemm_flops_tok = {"gemm_qkv": 2.0 * H * wl.n_qkv, "gemm_o": 2.0 * nq * d * H, "gemm_gate_up": 4.0 * H * F,
-                      "gemm_down": 2.0 * F * H}
+    gemm_flops_tok = {"gemm_qkv": 2.0 * H * wl.n_qkv * L, "gemm_o": 2.0 * nq * d * H * L,
+                      "gemm_gate_up": 4.0 * H * F * L, "gemm_down": 2.0 * F * H * L}      # per token, all layers
     two = 0 < split < T
-    attn_flops = (wl.attn_flops(0, split) + wl.attn_flops(split, T - split)) if two else wl.attn_flops(0, T)
+    attn_flops = L * ((wl.attn_flops(0, split) + wl.attn_flops(split, T - split)) if two else wl.attn_flops(0, T))
     e = 2 if wl.dtype == "bf16" else 4
     nkv = wl.n_kv_heads
-    bytes_tok = {"rmsnorm": 2 * H * e, "resid_norm": 4 * H * e, "residual": 3 * H * e,
-                 "rope_kv": (2 * (nq + nkv) * d + 2 * nkv * d) * e, "swiglu": 3 * F * e}
+    bytes_tok = {"rmsnorm": 2 * H * e, "resid_norm": 4 * H * e * (2 * L - 1), "residual": 3 * H * e,
+                 "rope_kv": (2 * (nq + nkv) * d + 2 * nkv * d) * e * L, "swiglu": 3 * F * e * L}
 
     def per_kernel(kd):
         out = {}
@@ -127,7 +140,7 @@ def main() -> int:
                 out[name] = {"ms": ms, "launches": n, "gbs": b * T / (ms * 1e-3) / 1e9}
         ms, n = kd["comm"]
         if n:
-            out["comm"] = {"ms": ms, "launches": n, "gbs": 2.0 * T * H * e / (ms * 1e-3) / 1e9}
+            out["comm"] = {"ms": ms, "launches": n, "gbs": 2.0 * L * T * H * e / (ms * 1e-3) / 1e9}
         return out
 
     pk_iso, pk_alone = per_kernel(k_iso), per_kernel(k_alone)
@@ -156,7 +169,7 @@ def main() -> int:
                            else "gemm_simple_kernel<float> (gate/up projection)"),
                 "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
                 "avg_launch_ms": dom_ms / dom_n, "flops_per_launch": flops_per_launch,
-                "launch_shape": {"M": T // dom_n, "N": 2 * F, "K": H, "launches_per_step": dom_n},
+                "launch_shape": {"M": T * L // dom_n, "N": 2 * F, "K": H, "launches_per_step": dom_n},
                 "measured": "HIP events around each launch, in its own stream, during ISO-scheduled steps",
                 "achieved_alone": ach_alone, "frac_alone": ach_alone / peak,
                 "avg_launch_ms_alone": dom_ms_alone / dom_n,
@@ -182,18 +195,19 @@ def main() -> int:
     if not args.no_cpu_baseline:
         cpu_baseline = time_oracle(wl, x_cpu, w_cpu, split)
 
-    layer_flops = wl.gemm_flops() + attn_flops
+    layer_flops = wl.gemm_flops() * L + attn_flops
     result = {
         "metric": "prefill tokens/s per layer shard (ISO vs unsplit) + attn/GEMM % MFMA peak",
-        "value": T / (t_iso * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "value": T / (t_iso * 1e-3), "unit": "tokens/s" if L == 1 else f"tokens/s through {L} layers", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": t_iso, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "hidden": H, "n_q_heads": nq, "n_kv_heads": nkv, "head_dim": d, "ffn": F,
-                   "seq": T, "split": split, "layers": 1, "comm": "d2h copy of [Tc,hidden] at both points",
+                   "seq": T, "split": split, "layers": L, "comm": "d2h copy of [Tc,hidden] at both points",
                    "schedule": "two streams, chunk per stream"},
         "tflops": layer_flops / (t_iso * 1e-3) / 1e12,
         "tflops_compute_only": layer_flops / (t_iso_nocomm * 1e-3) / 1e12,
         "unsplit_tokens_per_s": T / (t_unsplit * 1e-3),
+        "layer_tokens_per_s": T * L / (t_iso * 1e-3),
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "overlap": overlap,

@@ -366,3 +366,45 @@ def test_full_size_70b_tp8_4k_sampled_rows():
 @pytest.mark.parametrize("split", [4096, 4915, 5792])
 def test_full_size_70b_tp4_8k_sampled_rows(split):
     _sampled_parity("70b_tp4_8k", split, n_rows=48)
+
+
+def test_stack_at_70b_tp8_16k_shape_layer_by_layer():
+    """Three layers of the 80-layer 70B TP=8 stack shape at the full 16k prompt, split 8192/8192, chunks kept on
+    their streams across layers.  The bf16 bound is per layer, so each layer is checked from the GPU's own input
+    to that layer: the l-layer stack output is the oracle's input for layer l (sampled rows, plus all K/V rows)."""
+    wl = iso_inputs.WORKLOADS["70b_tp8_16k_stack"]
+    dt, T, split, L = wl.dtype, wl.seq, wl.split, 3
+    layers = [iso_inputs.make_layer(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, seed=1000 + l, dtype=dt)
+              for l in range(L)]
+    x0 = iso_inputs.make_hidden(T, wl.hidden, seed=0, dtype=dt)
+    sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
+    rows = iso_inputs.sample_rows(T, split, 24, seed=2)
+    layers_dev = [iso.upload_weights(w, dt) for w in layers]
+    errs = []
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, T) as ctx:
+        outs = []
+        for n in range(1, L + 1):           # n-layer stacks from the same input: outs[n-1] = input of layer n
+            xd = dev(x0, dt)
+            kcs = iso.DeviceArray((n, T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=NAN_BYTE)
+            vcs = iso.DeviceArray((n, T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=NAN_BYTE)
+            ctx.stack_prefill(layers_dev[:n], xd, kcs, vcs, T, split, iso.ISO_COMM_D2H)
+            ctx.sync()
+            outs.append(xd.numpy())
+            if n == L:
+                k_all, v_all = kcs.numpy(), vcs.numpy()
+        # the single-layer entry point must agree bit for bit with a one-layer stack
+        xd = dev(x0, dt)
+        kc = iso.DeviceArray((T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=NAN_BYTE)
+        vc = iso.DeviceArray((T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=NAN_BYTE)
+        ctx.layer_prefill(layers_dev[0], xd, kc, vc, T, split, iso.ISO_COMM_D2H)
+        ctx.sync()
+        np.testing.assert_array_equal(xd.numpy(), outs[0])
+    inputs = [x0] + outs[:-1]
+    for l in range(L):
+        ref = orc.layer_rows(h64(inputs[l], dt), oracle_weights(layers[l], dt), sh, rows)
+        err = orc.max_rel_err(h64(outs[l], dt)[rows], ref["x_out"])
+        ek = orc.max_rel_err(h64(k_all[l], dt), ref["k_cache"])
+        ev = orc.max_rel_err(h64(v_all[l], dt), ref["v_cache"])
+        errs.append((err, ek, ev))
+        assert err <= TOL_LAYER[dt] and ek <= TOL_LAYER[dt] and ev <= TOL_LAYER[dt], (l, err, ek, ev)
+    print("70b_tp8_16k_stack per-layer max_rel_err (x_out, k, v):", errs)
