@@ -98,6 +98,10 @@ def main() -> int:
     t_unsplit = timed(0, D2H, SER)                 # the pipeline ISO is compared with
     t_iso_nocomm = timed(split, NONE, OVL)
     t_unsplit_nocomm = timed(0, NONE, SER)
+    # the paper's remedy when communication dominates (Section 3.2): int8 payload, half the bytes
+    INT8 = iso.ISO_COMM_D2H_INT8
+    t_iso_int8 = timed(split, INT8, OVL)
+    t_unsplit_int8 = timed(0, INT8, SER)
 
     # ---- per-kernel durations, measured live with HIP events in the launch streams ----------------
     def kinds(sp, comm, sched, steps):
@@ -114,6 +118,7 @@ def main() -> int:
     k_iso = kinds(split, D2H, OVL, ksteps)           # as scheduled in the timed ISO steps
     k_alone = kinds(split, NONE, SER, ksteps)        # same launches, one stream, nothing concurrent
     k_comm = kinds(split, D2H, SER, ksteps)
+    k_int8 = kinds(split, INT8, SER, ksteps)
 
     H, F, d, nq = wl.hidden, wl.ffn, wl.head_dim, wl.n_q_heads
     gemm_flops_tok = {"gemm_qkv": 2.0 * H * wl.n_qkv * L, "gemm_o": 2.0 * nq * d * H * L,
@@ -210,6 +215,11 @@ def main() -> int:
         "layer_tokens_per_s": T * L / (t_iso * 1e-3),
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "int8_payload": {"t_iso_ms": t_iso_int8, "t_unsplit_ms": t_unsplit_int8,
+                         "tokens_per_s": T / (t_iso_int8 * 1e-3), "reduction_vs_unsplit": 1.0 - t_iso_int8 / t_unsplit_int8,
+                         "sum_copy_ms": k_int8["comm"][0], "sum_quant_ms": k_int8["quant"][0],
+                         "note": "partials quantised per token row to int8 before the copy (Section 3.2); "
+                                 "not the headline: the headline moves the bf16 partial"},
         "overlap": overlap,
         "kernels_in_iso_schedule": pk_iso,
         "kernels_alone": pk_alone,

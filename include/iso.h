@@ -45,8 +45,13 @@ typedef enum { ISO_F32 = 0, ISO_BF16 = 1 } iso_dtype;
 /* What stands at the two communication points of a layer (after o_proj, after down). */
 typedef enum {
     ISO_COMM_NONE = 0, /* nothing: compute only                                                      */
-    ISO_COMM_D2H = 1   /* copy the [Tc, hidden] partial to pinned host memory in the chunk's stream;  */
+    ISO_COMM_D2H = 1,  /* copy the [Tc, hidden] partial to pinned host memory in the chunk's stream;  */
                        /* the consumer kernel is behind the copy in stream order                      */
+    ISO_COMM_D2H_INT8 = 2 /* Section 3.2 (communication dominates): quantise the partial to int8 first.   */
+                       /* Per token row: scale = max|p|/127 (1 for a zero row), code = nearest-even(p/scale)   */
+                       /* clipped to +-127.  The copy moves Tc rows of hidden codes + the fp32 scale (row     */
+                       /* pitch hidden + 16 bytes); the layer continues with code*scale, the value a receiver */
+                       /* of the quantised payload would add to its residual stream.                          */
 } iso_comm;
 
 /* How the two chunks are issued (Section 1, Figure 1 (a) versus (d)). */
@@ -180,7 +185,7 @@ int iso_set_flags(iso_ctx *ctx, int flags);
 typedef enum {
     ISO_K_GEMM_QKV = 0, ISO_K_GEMM_O = 1, ISO_K_GEMM_GATE_UP = 2, ISO_K_GEMM_DOWN = 3, ISO_K_ATTN = 4,
     ISO_K_RMSNORM = 5, ISO_K_RESID_NORM = 6, ISO_K_RESIDUAL = 7, ISO_K_ROPE_KV = 8, ISO_K_SWIGLU = 9,
-    ISO_K_COMM = 10, ISO_K_COUNT = 11
+    ISO_K_COMM = 10, ISO_K_QUANT = 11, ISO_K_COUNT = 12
 } iso_kernel_kind;
 int iso_timing_enable(iso_ctx *ctx, int on);
 int iso_timing_read(iso_ctx *ctx, int kind, double *total_ms, int *launches);
@@ -201,7 +206,8 @@ int iso_copy_d2d(void *dst_dev, const void *src_dev, size_t bytes);
 int iso_stream_create(void **stream);                     /* non-blocking stream, default priority  */
 int iso_stream_destroy(void *stream);
 
-/* Pinned host buffer the context uses for ISO_COMM_D2H (2 * max_seq * hidden elements), for tests. */
+/* Pinned host buffer of the communication stand-in, for tests: two regions of max_seq * hidden elements
+ * (after o_proj, after down); with ISO_COMM_D2H_INT8 a region holds rows of hidden + 16 bytes. */
 void *iso_host_sink(iso_ctx *ctx);
 
 #ifdef __cplusplus

@@ -139,6 +139,29 @@ def swiglu(gate_up) -> np.ndarray:
     return silu(gu[..., :f]) * gu[..., f:]
 
 
+def quantize_rows(p):
+    """Int8 payload of a communication point (Section 3.2, "communication dominates": the data sent is
+    quantised to int8).  The paper does not give the quantiser; this build fixes it as symmetric per token
+    row: scale = max|p| / 127 (1 for an all-zero row), code = p / scale rounded to nearest, ties to even,
+    clipped to [-127, 127].  Returns (codes int8 [T,H], scales float64 [T])."""
+    p = _f64(p)
+    amax = np.max(np.abs(p), axis=-1)
+    scale = np.where(amax > 0, amax / 127.0, 1.0)
+    codes = np.clip(np.rint(p / scale[..., None]), -127, 127).astype(np.int8)
+    return codes, scale
+
+
+def quant_dequant_rows(p):
+    """What a receiver of the int8 payload adds to its residual stream: code * scale."""
+    codes, scale = quantize_rows(p)
+    return codes.astype(np.float64) * scale[..., None]
+
+
+def _comm(p, quant: bool):
+    """All-reduce over a world of one rank: the identity, optionally through the int8 payload."""
+    return quant_dequant_rows(p) if quant else p
+
+
 # ----------------------------------------------------------------------------- layer
 
 def _split_qkv(qkv: np.ndarray, sh: LayerShape):
@@ -150,15 +173,22 @@ def _split_qkv(qkv: np.ndarray, sh: LayerShape):
     return q, k, v
 
 
-def _mlp_block(x1: np.ndarray, w: Dict[str, np.ndarray], sh: LayerShape) -> np.ndarray:
+def mlp_partial(x1: np.ndarray, w: Dict[str, np.ndarray], sh: LayerShape) -> np.ndarray:
+    """Row-parallel partial of the MLP block: down(swiglu(gate_up(rmsnorm(x1))))."""
     y2 = rmsnorm(x1, w["g_mlp"], sh.rms_eps)
     a = swiglu(linear(y2, w["w_gate_up"]))
-    pm = linear(a, w["w_down"])          # row-parallel partial; all-reduce over one device = identity
-    return x1 + pm
+    return linear(a, w["w_down"])
 
 
-def layer_unsplit(x, w: Dict[str, np.ndarray], sh: LayerShape) -> Dict[str, np.ndarray]:
-    """One decoder-layer shard over the whole prompt (the pipeline ISO is compared with)."""
+def _mlp_block(x1: np.ndarray, w: Dict[str, np.ndarray], sh: LayerShape, quant: bool = False) -> np.ndarray:
+    pm = mlp_partial(x1, w, sh)          # all-reduce over one device = identity
+    return x1 + _comm(pm, quant)
+
+
+def layer_unsplit(x, w: Dict[str, np.ndarray], sh: LayerShape, quant: bool = False) -> Dict[str, np.ndarray]:
+    """One decoder-layer shard over the whole prompt (the pipeline ISO is compared with).
+    quant=True sends both partials through the int8 payload of Section 3.2 (per-row quantisation acts on
+    each token separately, so it commutes with the chunking)."""
     x = _f64(x)
     T = x.shape[0]
     pos = np.arange(T)
@@ -168,11 +198,11 @@ def layer_unsplit(x, w: Dict[str, np.ndarray], sh: LayerShape) -> Dict[str, np.n
     k = rope(k, pos, sh.rope_base)
     o = attention_full(q, k, v).reshape(T, sh.n_q_heads * sh.head_dim)
     pa = linear(o, w["w_o"])             # row-parallel partial
-    x1 = x + pa
-    return {"x_out": _mlp_block(x1, w, sh), "k_cache": k, "v_cache": v, "x1": x1, "attn": o}
+    x1 = x + _comm(pa, quant)
+    return {"x_out": _mlp_block(x1, w, sh, quant), "k_cache": k, "v_cache": v, "x1": x1, "attn": o, "pa": pa}
 
 
-def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split: int) -> Dict[str, np.ndarray]:
+def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split: int, quant: bool = False) -> Dict[str, np.ndarray]:
     """The same layer as two chunks [0,split) and [split,T) (Section 3.1).
 
     Chunk 0 writes its K/V rows into the cache and attends to them; chunk 1 then
@@ -196,13 +226,13 @@ def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split: int) -> Dict[s
         v_cache[lo:hi] = v
         o = attention_chunk(q, k_cache, v_cache, q_offset=lo, kv_len=hi)
         pa = linear(o.reshape(hi - lo, -1), w["w_o"])
-        x1 = xc + pa
+        x1 = xc + _comm(pa, quant)
         x1_all[lo:hi] = x1
-        x_out[lo:hi] = _mlp_block(x1, w, sh)
+        x_out[lo:hi] = _mlp_block(x1, w, sh, quant)
     return {"x_out": x_out, "k_cache": k_cache, "v_cache": v_cache, "x1": x1_all}
 
 
-def layer_rows(x, w: Dict[str, np.ndarray], sh: LayerShape, rows: Sequence[int]) -> Dict[str, np.ndarray]:
+def layer_rows(x, w: Dict[str, np.ndarray], sh: LayerShape, rows: Sequence[int], quant: bool = False) -> Dict[str, np.ndarray]:
     """Exact output rows `rows` of the layer, without computing the others.
 
     Output row p depends on x[p] and on the K/V rows 0..p only, so K/V are computed
@@ -223,8 +253,8 @@ def layer_rows(x, w: Dict[str, np.ndarray], sh: LayerShape, rows: Sequence[int])
     for r, p in enumerate(rows):
         o[r] = attention_chunk(q[r:r + 1], k, v, q_offset=int(p), kv_len=int(p) + 1)[0]
     pa = linear(o.reshape(len(rows), nq * d), w["w_o"])
-    x1 = x[rows] + pa
-    return {"x_out": _mlp_block(x1, w, sh), "k_cache": k, "v_cache": v, "x1": x1, "rows": rows}
+    x1 = x[rows] + _comm(pa, quant)
+    return {"x_out": _mlp_block(x1, w, sh, quant), "k_cache": k, "v_cache": v, "x1": x1, "rows": rows, "pa": pa}
 
 
 # ----------------------------------------------------------------------------- metric

@@ -24,7 +24,7 @@ from . import build as _build
 ISO_OK = 0
 ISO_ERR_NULL, ISO_ERR_SHAPE, ISO_ERR_DTYPE, ISO_ERR_SPLIT, ISO_ERR_WORKSPACE, ISO_ERR_HIP = -1, -2, -3, -4, -5, -6
 ISO_F32, ISO_BF16 = 0, 1
-ISO_COMM_NONE, ISO_COMM_D2H = 0, 1
+ISO_COMM_NONE, ISO_COMM_D2H, ISO_COMM_D2H_INT8 = 0, 1, 2
 ISO_SCHED_OVERLAP, ISO_SCHED_SERIAL = 0, 1
 ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN, ISO_FLAG_GEMM_STAGED, ISO_FLAG_NO_FUSE, ISO_FLAG_ATTN_STAGED = 1, 2, 4, 8, 16
 
@@ -37,7 +37,7 @@ EXPORTS = [
     "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
 ]
 KERNEL_KINDS = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn", "rmsnorm", "resid_norm", "residual",
-                "rope_kv", "swiglu", "comm"]
+                "rope_kv", "swiglu", "comm", "quant"]
 DTYPE_BYTES = {"f32": 4, "bf16": 2}
 _NP_STORAGE = {"f32": np.float32, "bf16": np.uint16}
 

@@ -171,6 +171,68 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(T *qkv, T *__restrict__ k_
     }
 }
 
+// Int8 payload for the communication point (paper Section 3.2, "communication dominates": the partial is
+// quantised before it is sent).  One workgroup per token row: scale = max|p| / 127 (1 if the row is zero),
+// code = round-to-nearest-even(p / scale) in [-127, 127].  Output row = H codes followed by the fp32 scale
+// (row pitch H + 16 bytes, so one contiguous copy moves codes and scales).  The partial is rewritten in place
+// with code * scale: that is what a receiver of the quantised payload would add to its residual stream.
+template <typename T>
+__global__ __launch_bounds__(256) void quant_rows_kernel(T *part, signed char *__restrict__ q8, int H) {
+    constexpr int VEC = 16 / sizeof(T);
+    constexpr int CACHE = 4;
+    const int tid = threadIdx.x;
+    const int nvec = H / VEC;
+    const size_t row = (size_t)blockIdx.x * H;
+    signed char *qrow = q8 + (size_t)blockIdx.x * (H + 16);
+    float vals[CACHE][VEC];
+    float amax = 0.f;
+#pragma unroll
+    for (int c = 0; c < CACHE; ++c) {
+        const int idx = tid + c * 256;
+        if (idx < nvec) {
+            load16<T>(part + row + (size_t)idx * VEC, vals[c]);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) amax = fmaxf(amax, fabsf(vals[c][i]));
+        }
+    }
+    for (int idx = tid + CACHE * 256; idx < nvec; idx += 256) {
+        float xv[VEC];
+        load16<T>(part + row + (size_t)idx * VEC, xv);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) amax = fmaxf(amax, fabsf(xv[i]));
+    }
+    __shared__ float red[4];
+    amax = iso_wave_max(amax);
+    if ((tid & 63) == 0) red[tid >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float scale = amax > 0.f ? amax / 127.0f : 1.0f;
+    if (tid == 0) *reinterpret_cast<float *>(qrow + H) = scale;
+    auto emit = [&](int idx, float (&v)[VEC]) {
+        signed char codes[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            float q = rintf(v[i] / scale);
+            q = fminf(fmaxf(q, -127.f), 127.f);
+            codes[i] = (signed char)(int)q;
+            v[i] = q * scale;
+        }
+        if (VEC == 8) *reinterpret_cast<uint2 *>(qrow + (size_t)idx * VEC) = *reinterpret_cast<const uint2 *>(codes);
+        else *reinterpret_cast<unsigned int *>(qrow + (size_t)idx * VEC) = *reinterpret_cast<const unsigned int *>(codes);
+        store16<T>(part + row + (size_t)idx * VEC, v);
+    };
+#pragma unroll
+    for (int c = 0; c < CACHE; ++c) {
+        const int idx = tid + c * 256;
+        if (idx < nvec) emit(idx, vals[c]);
+    }
+    for (int idx = tid + CACHE * 256; idx < nvec; idx += 256) {
+        float xv[VEC];
+        load16<T>(part + row + (size_t)idx * VEC, xv);
+        emit(idx, xv);
+    }
+}
+
 template <typename T> __device__ __forceinline__ float silu_f(float z);
 template <> __device__ __forceinline__ float silu_f<float>(float z) { return z / (1.0f + expf(-z)); }
 template <> __device__ __forceinline__ float silu_f<bf16_t>(float z) { return z / (1.0f + __expf(-z)); }
@@ -238,5 +300,14 @@ hipError_t iso_launch_swiglu(int dtype, const void *gu, void *a, int T, int F, h
         hipLaunchKernelGGL(swiglu_kernel<float>, grid, block, 0, s, (const float *)gu, (float *)a, n_units, F);
     else
         hipLaunchKernelGGL(swiglu_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)gu, (bf16_t *)a, n_units, F);
+    return hipGetLastError();
+}
+
+hipError_t iso_launch_quant_rows(int dtype, void *part, void *q8, int T, int H, hipStream_t s) {
+    dim3 grid(T), block(256);
+    if (dtype == ISO_F32)
+        hipLaunchKernelGGL(quant_rows_kernel<float>, grid, block, 0, s, (float *)part, (signed char *)q8, H);
+    else
+        hipLaunchKernelGGL(quant_rows_kernel<bf16_t>, grid, block, 0, s, (bf16_t *)part, (signed char *)q8, H);
     return hipGetLastError();
 }

@@ -40,7 +40,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 int n_qkv(const iso_cfg &c) { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
 
 struct WsLayout {
-    size_t y, qkv, attn, part, gu, act, x1f, total;
+    size_t y, qkv, attn, part, gu, act, x1f, q8, total;
 };
 
 WsLayout ws_layout(const iso_cfg &c) {
@@ -55,6 +55,7 @@ WsLayout ws_layout(const iso_cfg &c) {
     l.gu = take(t * 2 * c.ffn);
     l.act = take(t * c.ffn);
     l.x1f = take(c.dtype == ISO_BF16 ? t * c.hidden * 2 : 0);   // fp32 = two bf16 slots per element
+    l.q8 = take((t * (c.hidden + 16) + e - 1) / e);
     l.total = off;
     return l;
 }
@@ -140,6 +141,25 @@ int attention(iso_ctx *ctx, const void *q, int q_stride, const void *kc, const v
         if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "%s launch: %s", what, hipGetErrorString(e_)); \
     } while (0)
 
+// Communication point of one chunk: nothing, the [n, H] partial as it is, or its int8 codes + row scales.
+// `which` = 0 after o_proj, 1 after down; the host sink keeps the two points apart.
+int comm_point(iso_ctx *ctx, int comm, int which, int lo, int n, hipStream_t s) {
+    const iso_cfg &c = ctx->cfg;
+    const size_t e = ctx->elt, H = (size_t)c.hidden;
+    char *partr = (char *)ctx->part + (size_t)lo * H * e;
+    char *sink = (char *)ctx->host_sink + (size_t)which * c.max_seq * H * e;
+    if (comm == ISO_COMM_D2H) {
+        Timed t_(ctx, ISO_K_COMM, s);
+        HIP_TRY(hipMemcpyAsync(sink + (size_t)lo * H * e, partr, (size_t)n * H * e, hipMemcpyDeviceToHost, s));
+    } else if (comm == ISO_COMM_D2H_INT8) {
+        signed char *q = ctx->q8 + (size_t)lo * (H + 16);
+        LAUNCH_TRY(ISO_K_QUANT, s, iso_launch_quant_rows(c.dtype, partr, q, n, (int)H, s), "quantise");
+        Timed t_(ctx, ISO_K_COMM, s);
+        HIP_TRY(hipMemcpyAsync(sink + (size_t)lo * (H + 16), q, (size_t)n * (H + 16), hipMemcpyDeviceToHost, s));
+    }
+    return ISO_OK;
+}
+
 // One chunk = token rows [lo, lo + n).
 struct Chunk {
     int lo, n;
@@ -177,11 +197,8 @@ int attn_block_tail(iso_ctx *ctx, const iso_weights *w, void *kc, void *vc, cons
     char *partr = at(ctx->part, ck.lo, H, e);
     ISO_TRY(attention(ctx, qkvr, NQKV, kc, vc, attnr, ck.n, ck.lo, ck.lo + ck.n, ck.s));
     ISO_TRY(gemm(ctx, ISO_K_GEMM_O, attnr, w->w_o, partr, ck.n, H, NQD, ck.s));
-    if (comm == ISO_COMM_D2H) {
-        Timed t_(ctx, ISO_K_COMM, ck.s);
-        HIP_TRY(hipMemcpyAsync(at(ctx->host_sink, ck.lo, H, e), partr, (size_t)ck.n * H * e, hipMemcpyDeviceToHost, ck.s));
-    }
-    return ISO_OK;
+    (void)partr;
+    return comm_point(ctx, comm, 0, ck.lo, ck.n, ck.s);
 }
 
 int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int comm) {
@@ -208,12 +225,7 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
         LAUNCH_TRY(ISO_K_SWIGLU, ck.s, iso_launch_swiglu(c.dtype, gur, actr, ck.n, F, ck.s), "swiglu");
     }
     ISO_TRY(gemm(ctx, ISO_K_GEMM_DOWN, actr, w->w_down, partr, ck.n, H, F, ck.s));
-    if (comm == ISO_COMM_D2H) {
-        Timed t_(ctx, ISO_K_COMM, ck.s);
-        HIP_TRY(hipMemcpyAsync(at((char *)ctx->host_sink + (size_t)c.max_seq * H * e, ck.lo, H, e), partr,
-                               (size_t)ck.n * H * e, hipMemcpyDeviceToHost, ck.s));
-    }
-    return ISO_OK;
+    return comm_point(ctx, comm, 1, ck.lo, ck.n, ck.s);
 }
 
 int final_residual(iso_ctx *ctx, void *x, const Chunk &ck) {
@@ -239,7 +251,8 @@ int check_layer_args(iso_ctx *ctx, const iso_weights *layers, int n_layers, void
     if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
     if (T > ctx->cfg.max_seq) return fail(ISO_ERR_WORKSPACE, "T=%d exceeds max_seq=%d", T, ctx->cfg.max_seq);
     if (split < 0 || split > T) return fail(ISO_ERR_SPLIT, "split=%d outside [0, %d]", split, T);
-    if (comm != ISO_COMM_NONE && comm != ISO_COMM_D2H) return fail(ISO_ERR_SHAPE, "unknown comm mode %d", comm);
+    if (comm != ISO_COMM_NONE && comm != ISO_COMM_D2H && comm != ISO_COMM_D2H_INT8)
+        return fail(ISO_ERR_SHAPE, "unknown comm mode %d", comm);
     if (sched != ISO_SCHED_OVERLAP && sched != ISO_SCHED_SERIAL) return fail(ISO_ERR_SHAPE, "unknown schedule %d", sched);
     return ISO_OK;
 }
@@ -343,6 +356,7 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
         ctx->y = b + l.y; ctx->qkv = b + l.qkv; ctx->attn = b + l.attn;
         ctx->part = b + l.part; ctx->gu = b + l.gu; ctx->act = b + l.act;
         ctx->x1f = (float *)(b + l.x1f);
+        ctx->q8 = (signed char *)(b + l.q8);
         if (!hip_ok(hipMalloc((void **)&ctx->rope_cos, table * sizeof(float)), "hipMalloc(rope cos)")) break;
         if (!hip_ok(hipMalloc((void **)&ctx->rope_sin, table * sizeof(float)), "hipMalloc(rope sin)")) break;
         {   // rotary table: angles in double on the host, stored as fp32

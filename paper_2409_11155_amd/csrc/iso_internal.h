@@ -29,6 +29,7 @@ struct iso_ctx {
     void *part;        // [max_seq, hidden]   row-parallel partial (o_proj, then down)
     void *gu;          // [max_seq, 2*ffn]
     void *act;         // [max_seq, ffn]
+    signed char *q8;   // [max_seq, hidden + 16] int8 codes + fp32 scale per row (ISO_COMM_D2H_INT8)
     float *x1f;        // [max_seq, hidden] fp32: residual stream between the two blocks of a bf16 layer
     float *rope_cos;   // [max_seq, d/2]
     float *rope_sin;   // [max_seq, d/2]
@@ -47,6 +48,7 @@ hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta_or_nul
                               hipStream_t s);   // x_in_f32 / x_out_f32: bf16 layers only, residual in an fp32 side buffer
 hipError_t iso_launch_rope_kv(int dtype, void *qkv, void *k_cache, void *v_cache, const float *cos_t,
                               const float *sin_t, int Tc, int q_offset, int nq, int nkv, int d, hipStream_t s);
+hipError_t iso_launch_quant_rows(int dtype, void *part, void *q8, int T, int H, hipStream_t s);
 hipError_t iso_launch_swiglu(int dtype, const void *gu, void *a, int T, int F, hipStream_t s);
 hipError_t iso_launch_gemm_simple(int dtype, const void *a, const void *w, void *c, int M, int N, int K,
                                   hipStream_t s);

@@ -408,3 +408,94 @@ def test_stack_at_70b_tp8_16k_shape_layer_by_layer():
         errs.append((err, ek, ev))
         assert err <= TOL_LAYER[dt] and ek <= TOL_LAYER[dt] and ev <= TOL_LAYER[dt], (l, err, ek, ev)
     print("70b_tp8_16k_stack per-layer max_rel_err (x_out, k, v):", errs)
+
+
+# ------------------------------------------------------------------------------ int8 payload (Section 3.2)
+
+def _int8_bound(ref, w64, sh, dt):
+    """Extra error the int8 payload may add on top of the layer bound: where the GPU's partial and the oracle's
+    differ by rounding noise across a .5 boundary they take neighbouring codes, i.e. differ by one step
+    (scale = row max / 127) at that element, once per communication point."""
+    pm = orc.mlp_partial(ref["x1"], w64, sh)
+    step = np.abs(ref["pa"]).max(axis=1) / 127.0 + np.abs(pm).max(axis=1) / 127.0
+    rms = float(np.sqrt(np.mean(ref["x_out"] ** 2)))
+    return float(step.max()) / rms, pm
+
+
+def _check_sink_codes(ctx, T, H, pa, pm, dt, rows=None):
+    """The pinned sink holds rows of H int8 codes + fp32 scale (pitch H + 16) for both points."""
+    import ctypes
+    e = 2 if dt == "bf16" else 4
+    region = ctx.cfg.max_seq * H * e
+    raw = np.frombuffer((ctypes.c_ubyte * (2 * region)).from_address(ctx.host_sink()), dtype=np.uint8)
+    for which, part in ((0, pa), (1, pm)):
+        blk = raw[which * region: which * region + T * (H + 16)].reshape(T, H + 16)
+        codes = blk[:, :H].view(np.int8)
+        scales = blk[:, H:H + 4].copy().view(np.float32)[:, 0]
+        if rows is not None:
+            codes, scales = codes[rows], scales[rows]
+        ref_codes, ref_scales = orc.quantize_rows(part)
+        tol_s = 1e-3 if dt == "f32" else 2e-2     # a code flip at the first point shifts the second partial a little
+        np.testing.assert_allclose(scales, ref_scales, rtol=tol_s)
+        d = np.abs(codes.astype(np.int32) - ref_codes.astype(np.int32))
+        lim = 1 if dt == "f32" else 2           # bf16 partials carry ~1 % noise: up to ~1.3 codes at |code| = 127
+        assert d.max() <= lim, d.max()
+        if dt == "f32":
+            assert np.mean(d > 0) < 0.01
+
+
+def test_tiny_f32_layer_int8_payload():
+    wl = iso_inputs.WORKLOADS["tiny_f32"]
+    x, w = iso_inputs.make_workload_inputs(wl, seed=0)
+    sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
+    w64 = oracle_weights(w, "f32")
+    ref = orc.layer_unsplit(h64(x, "f32"), w64, sh, quant=True)
+    extra, pm = _int8_bound(ref, w64, sh, "f32")
+    w_dev = iso.upload_weights(w, "f32")
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, "f32", wl.seq) as ctx:
+        for split in (0, 64, 37):
+            for sched in (iso.ISO_SCHED_OVERLAP, iso.ISO_SCHED_SERIAL):
+                out, _, _ = run_layer(ctx, w_dev, x, "f32", wl.seq, split, wl.n_kv_heads, wl.head_dim, wl.seq,
+                                      iso.ISO_COMM_D2H_INT8, sched, poison=True)
+                got = f64(out)
+                err = orc.max_rel_err(got, ref["x_out"])
+                assert err <= TOL_LAYER["f32"] + extra, (split, err, extra)
+                # away from code flips the result is as tight as without the payload
+                close = np.abs(got - ref["x_out"]) <= 1e-4 * np.maximum(np.abs(ref["x_out"]), 1.0)
+                assert close.mean() > 0.99
+                _check_sink_codes(ctx, wl.seq, wl.hidden, ref["pa"], pm, "f32")
+
+
+def test_small_bf16_layer_int8_payload():
+    hidden, nq, nkv, d, ffn, T, dt = 512, 4, 1, 128, 768, 300, "bf16"
+    w = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=11, dtype=dt)
+    x = iso_inputs.make_hidden(T, hidden, seed=11, dtype=dt)
+    sh = shape_of(hidden, nq, nkv, d, ffn)
+    w64 = oracle_weights(w, dt)
+    ref = orc.layer_unsplit(h64(x, dt), w64, sh, quant=True)
+    extra, pm = _int8_bound(ref, w64, sh, dt)
+    w_dev = iso.upload_weights(w, dt)
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, 320) as ctx:
+        for split in (0, 130):
+            out, _, _ = run_layer(ctx, w_dev, x, dt, T, split, nkv, d, 320, iso.ISO_COMM_D2H_INT8, poison=True)
+            err = orc.max_rel_err(f64(out), ref["x_out"])
+            assert err <= TOL_LAYER["bf16"] + extra, (split, err, extra)
+            _check_sink_codes(ctx, T, hidden, ref["pa"], pm, dt)
+
+
+def test_full_size_30b_tp4_2k_int8_payload_sampled_rows():
+    wl = iso_inputs.WORKLOADS["30b_tp4_2k"]
+    dt = wl.dtype
+    x, w = iso_inputs.make_workload_inputs(wl, seed=0)
+    rows = iso_inputs.sample_rows(wl.seq, wl.split, 64, seed=0)
+    sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
+    w64 = oracle_weights(w, dt)
+    ref = orc.layer_rows(h64(x, dt), w64, sh, rows, quant=True)
+    extra, pm = _int8_bound(ref, w64, sh, dt)
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, wl.seq) as ctx:
+        out, _, _ = run_layer(ctx, iso.upload_weights(w, dt), x, dt, wl.seq, wl.split, wl.n_kv_heads, wl.head_dim,
+                              wl.seq, iso.ISO_COMM_D2H_INT8, poison=True)
+        err = orc.max_rel_err(f64(out)[rows], ref["x_out"])
+        print("30b_tp4_2k int8 payload: max_rel_err", err, "bound", TOL_LAYER[dt] + extra)
+        assert err <= TOL_LAYER[dt] + extra
+        _check_sink_codes(ctx, wl.seq, wl.hidden, ref["pa"], pm, dt, rows=rows)

@@ -388,3 +388,40 @@ def test_bf16_storage_round_trip_is_round_to_nearest_even():
     np.testing.assert_array_equal(back[:3], [1.0, 1.0, 1.015625])
     assert abs(back[3] + 3.14159) <= 2.0 ** -7 and back[4] == 65536.0 and back[5] == 0.0
     np.testing.assert_array_equal(iso_inputs.f32_to_bf16_bits(back), bits)
+
+
+# ------------------------------------------------------------------ int8 payload (Section 3.2)
+
+def test_quantize_rows_hand_values_and_properties():
+    p = np.array([[127.0, -63.5, 0.4, 0.5, 1.5, 2.5, -2.5, 0.0],     # scale 1: ties go to the even code
+                  [0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0],          # zero row: scale 1, codes 0
+                  [-2.54, 1.27, 0.01, 0.0, 0.0, 0.0, 0.0, 0.0]])     # scale 0.02
+    codes, scale = orc.quantize_rows(p)
+    np.testing.assert_array_equal(codes[0], [127, -64, 0, 0, 2, 2, -2, 0])
+    np.testing.assert_array_equal(codes[1], 0)
+    assert scale[0] == 1.0 and scale[1] == 1.0 and scale[2] == pytest.approx(0.02, rel=1e-15)
+    np.testing.assert_array_equal(codes[2][:3], [-127, 64, 0])        # 63.5 -> 64 (even), 0.5 -> 0 (even)
+    x = RNG.standard_normal((9, 64)) * np.logspace(-3, 3, 9)[:, None]
+    dq = orc.quant_dequant_rows(x)
+    amax = np.abs(x).max(axis=1, keepdims=True)
+    assert np.all(np.abs(dq - x) <= amax / 127.0 / 2 * (1 + 1e-12))   # at most half a step
+    np.testing.assert_allclose(orc.quant_dequant_rows(dq), dq, rtol=1e-12, atol=0)   # idempotent
+    np.testing.assert_array_equal(orc.quantize_rows(-x)[0], -orc.quantize_rows(x)[0])  # symmetric
+    # the row maximum is always hit exactly (code +-127)
+    assert np.all(np.abs(orc.quantize_rows(x)[0]).max(axis=1) == 127)
+
+
+def test_quantised_layer_stays_split_invariant_and_close_to_the_exact_layer():
+    wl, x, w, sh = _tiny()
+    exact = orc.layer_unsplit(x, w, sh)["x_out"]
+    q = orc.layer_unsplit(x, w, sh, quant=True)["x_out"]
+    for s in (1, 37, 64, 127):
+        assert orc.max_rel_err(orc.layer_iso(x, w, sh, s, quant=True)["x_out"], q) < 1e-12
+    # restricted to some rows the matrix products sum in another order; a partial that sits within 1e-16 of a
+    # rounding boundary may then take the neighbouring code: all but a handful of elements agree exactly, and
+    # those differ by less than one quantisation step
+    r = orc.layer_rows(x, w, sh, [0, 5, 127], quant=True)["x_out"]
+    diff = np.abs(r - q[[0, 5, 127]])
+    assert np.mean(diff > 1e-9) < 0.01 and diff.max() < np.abs(q).max() / 127.0
+    err = orc.max_rel_err(q, exact)
+    assert 1e-4 < err < 3e-2          # the payload costs something, but only about half a step of 1/127
