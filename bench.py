@@ -32,6 +32,7 @@ def parse_args():
     ap.add_argument("--workload", default="30b_tp4_2k")
     ap.add_argument("--split", type=int, default=-1, help="split point (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--flags", type=int, default=0, help="kernel-choice flags (ISO_FLAG_*), for ablations")
     ap.add_argument("--layers", type=int, default=0, help="layers of a stack workload (default: the workload's)")
     ap.add_argument("--distinct-layers", type=int, default=4,
                     help="a stack draws this many distinct weight sets on the host and gives every layer its own "
@@ -70,6 +71,7 @@ def main() -> int:
     vc = iso.DeviceArray((L, T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=0)
     cfg = iso.make_cfg(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, T)
     ctx = iso.Context(cfg)
+    ctx.set_flags(args.flags)
     K, W = args.steps, args.warmup
 
     def run(n, sp, comm, sched):

@@ -173,7 +173,8 @@ enum {
     ISO_FLAG_SIMPLE_ATTN = 2, /* one-wave-per-row attention instead of the MFMA attention  */
     ISO_FLAG_GEMM_STAGED = 4, /* register-staged 128x128 MFMA GEMM instead of the direct-to-LDS one */
     ISO_FLAG_NO_FUSE = 8,     /* gate/up projection and SwiGLU as two kernels instead of one        */
-    ISO_FLAG_ATTN_STAGED = 16 /* register-staged MFMA attention instead of the direct-to-LDS one    */
+    ISO_FLAG_ATTN_STAGED = 16,/* register-staged MFMA attention instead of the direct-to-LDS one    */
+    ISO_FLAG_NO_STREAMK = 32  /* never pick the stream-K launch of the direct-to-LDS GEMM by itself  */
     /* bits 8..11: tile variant of the direct-to-LDS GEMM (0 = chosen from the shape) */
 };
 int iso_set_flags(iso_ctx *ctx, int flags);

@@ -27,6 +27,7 @@ ISO_F32, ISO_BF16 = 0, 1
 ISO_COMM_NONE, ISO_COMM_D2H, ISO_COMM_D2H_INT8 = 0, 1, 2
 ISO_SCHED_OVERLAP, ISO_SCHED_SERIAL = 0, 1
 ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN, ISO_FLAG_GEMM_STAGED, ISO_FLAG_NO_FUSE, ISO_FLAG_ATTN_STAGED = 1, 2, 4, 8, 16
+ISO_FLAG_NO_STREAMK = 32
 
 EXPORTS = [
     "iso_validate_cfg", "iso_plan_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",

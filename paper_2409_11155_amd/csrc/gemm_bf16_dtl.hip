@@ -18,16 +18,18 @@
 //   * Epilogue: accumulators -> bf16 -> LDS (per-wave region) -> 16-byte row-contiguous global stores.
 // Requires K % 64 == 0, N % 8 == 0 and M*K, N*K < 2^31 elements; other shapes take the 128x128 staged kernel.
 #include "iso_internal.h"
+#include <type_traits>
 
 namespace {
 
 constexpr int BK = 64;                 // k slice: 128 bytes per row
 constexpr int ROW_BYTES = BK * 2;
+constexpr int SK_HDR = 4096;           // stream-K workspace: flag words first, partial-sum slots behind
+constexpr int SK_MAX_WG = 512;
+constexpr int SK_COHERENT = 1 | 16;    // buffer cache policy bits sc0 | sc1: system scope, bypasses the XCD-local L2
+constexpr unsigned SK_SPIN_LIMIT = 4000000u;   // bounded wait (about 2-4 s) so no wave can spin forever
 
-template <int SWZ> __device__ __forceinline__ int swz(int row) {
-    if (SWZ == 0) return row & 7;
-    return (row >> 1) & 7;
-}
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
 template <int BM, int BN, int WM, int WN> struct DtlCfg {
     static constexpr int NWAVES = WM * WN;
@@ -39,6 +41,7 @@ template <int BM, int BN, int WM, int WN> struct DtlCfg {
     static constexpr int CP = WTN + 8;                                          // epilogue LDS row pitch (elements)
     static constexpr int EPI_BYTES = NWAVES * WTM * CP * 2;
     static constexpr int LDS_BYTES = (2 * STAGE > EPI_BYTES) ? 2 * STAGE : EPI_BYTES;
+    static constexpr size_t SLOT_BYTES = (size_t)BM * BN * 4;                   // one fp32 partial tile
     static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "wave-loads must divide evenly");
 };
 
@@ -47,32 +50,32 @@ template <int BM, int BN, int WM, int WN> struct DtlCfg {
 // blocks alternate gate / up for the same 32 MLP columns; a lane then holds gate and up of one output element
 // in the same register slot of two neighbouring accumulators and the activation needs no data exchange and
 // no rounding of the projection output.  N is 2F and the output row stride is F.
-template <int BM, int BN, int WM, int WN, int SWZ, bool SWIGLU>
+//
+// SK = true (stream-K): the grid is one workgroup per compute unit and the (tile, k-slice) units are dealt out in
+// equal contiguous spans, so a launch whose tile count does not fill the chip still keeps every unit busy.  A span
+// that stops inside a tile leaves an fp32 partial tile in the workspace slot of its workgroup and raises that
+// workgroup's flag; the workgroup that reaches the tile's last k-slice adds the partials (in workgroup order, so
+// the sum is reproducible) and writes the tile.  Every workgroup does its partial segment FIRST and only then its
+// finishing segments (the one that needs partials last), and a finisher only ever waits for workgroups with a lower index, which the dispatcher
+// started earlier and which never wait before raising their flag: the waits always end.  They are bounded as
+// well: a wait that exceeds the spin limit reports through *sk_err and carries on.
+template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE, bool SK>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_t *__restrict__ A,
                                                                      const bf16_t *__restrict__ W,
                                                                      bf16_t *__restrict__ C, int M, int N, int K,
-                                                                     int tiles_m, int tiles_n) {
+                                                                     int tiles_m, int tiles_n,
+                                                                     unsigned char *sk_ws, unsigned sk_epoch,
+                                                                     unsigned *sk_err, int sk_team, int sk_grouped) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource builtins exist in the device pass only
     using Cfg = DtlCfg<BM, BN, WM, WN>;
     constexpr int NWAVES = Cfg::NWAVES, A_BYTES = Cfg::A_BYTES, STAGE = Cfg::STAGE;
     constexpr int A_LOADS = Cfg::A_LOADS, W_LOADS = Cfg::W_LOADS, TM = Cfg::TM, TN = Cfg::TN;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
-    // workgroup -> tile: contiguous tile range per XCD (ids go round-robin over 8 XCDs), groups of 8 tile rows
-    int pid = blockIdx.x;
     const int nt = tiles_m * tiles_n;
-    const int per_xcd = nt / 8;
-    if (pid < per_xcd * 8) pid = (pid % 8) * per_xcd + pid / 8;
-    constexpr int GROUP = 8;
-    const int width = GROUP * tiles_n;
-    const int group_id = pid / width;
-    const int first_m = group_id * GROUP;
-    const int gsize = min(tiles_m - first_m, GROUP);
-    const int tile_m = first_m + (pid % width) % gsize;
-    const int tile_n = (pid % width) / gsize;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nk = K / BK;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS bases of the wave-loads stay scalar
     const int wm = wave / WN, wn = wave % WN;
     const int lrow = lane & 31, lgrp = lane >> 5;
 
@@ -83,28 +86,34 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
         __builtin_amdgcn_make_buffer_rsrc((void *)A, 0, (int)((uint32_t)M * (uint32_t)K * 2u), 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w =
         __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (int)((uint32_t)N * (uint32_t)K * 2u), 0x00020000);
+    int m0 = 0, n0 = 0, tile_n = 0;
     uint32_t a_off[A_LOADS], w_off[W_LOADS];
+    auto set_tile = [&](int tile_m, int tile_n_) {
+        tile_n = tile_n_;
+        m0 = tile_m * BM;
+        n0 = tile_n * BN;
 #pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) {
-        const int r = (wave + NWAVES * i) * 8 + ld_row;
-        const int chunk = ld_slot ^ swz<SWZ>(r);
-        a_off[i] = ((uint32_t)min(m0 + r, M - 1) * (uint32_t)K + chunk * 8) * 2u;
-    }
-#pragma unroll
-    for (int i = 0; i < W_LOADS; ++i) {
-        const int r = (wave + NWAVES * i) * 8 + ld_row;
-        const int chunk = ld_slot ^ swz<SWZ>(r);
-        int grow;
-        if (SWIGLU) {
-            const int F = N / 2;
-            const int jt = (r % Cfg::WTN) / 32;          // MFMA column block inside the wave tile
-            const int f = tile_n * (BN / 2) + (r / Cfg::WTN) * (Cfg::WTN / 2) + (jt / 2) * 32 + (r % 32);
-            grow = (jt & 1) * F + min(f, F - 1);
-        } else {
-            grow = min(n0 + r, N - 1);
+        for (int i = 0; i < A_LOADS; ++i) {
+            const int r = (wave + NWAVES * i) * 8 + ld_row;
+            const int chunk = ld_slot ^ swz(r);
+            a_off[i] = ((uint32_t)min(m0 + r, M - 1) * (uint32_t)K + chunk * 8) * 2u;
         }
-        w_off[i] = ((uint32_t)grow * (uint32_t)K + chunk * 8) * 2u;
-    }
+#pragma unroll
+        for (int i = 0; i < W_LOADS; ++i) {
+            const int r = (wave + NWAVES * i) * 8 + ld_row;
+            const int chunk = ld_slot ^ swz(r);
+            int grow;
+            if (SWIGLU) {
+                const int F = N / 2;
+                const int jt = (r % Cfg::WTN) / 32;          // MFMA column block inside the wave tile
+                const int f = tile_n * (BN / 2) + (r / Cfg::WTN) * (Cfg::WTN / 2) + (jt / 2) * 32 + (r % 32);
+                grow = (jt & 1) * F + min(f, F - 1);
+            } else {
+                grow = min(n0 + r, N - 1);
+            }
+            w_off[i] = ((uint32_t)grow * (uint32_t)K + chunk * 8) * 2u;
+        }
+    };
     auto issue = [&](int stage, int k0) {
         unsigned char *base = lds + stage * STAGE;
 #pragma unroll
@@ -125,25 +134,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
     for (int i = 0; i < TM; ++i) {
         const int r = wm * Cfg::WTM + i * 32 + lrow;
         a_row_off[i] = r * ROW_BYTES;
-        a_sw[i] = swz<SWZ>(r);
+        a_sw[i] = swz(r);
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int r = wn * Cfg::WTN + j * 32 + lrow;
         w_row_off[j] = A_BYTES + r * ROW_BYTES;
-        w_sw[j] = swz<SWZ>(r);
+        w_sw[j] = swz(r);
     }
 
     f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // ---- main loop
-    const int nk = K / BK;
     bf16x8_t af[2][TM], wf[2][TN];
     auto read_frags = [&](const unsigned char *base, int buf, int ks) {
         const int chunk = ks * 2 + lgrp;
@@ -162,91 +162,278 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], wf[buf][j], acc[i][j], 0, 0, 0);
     };
 
-    issue(0, 0);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    read_frags(lds, 0, 0);
-    if (nk > 1) issue(1, BK);
-    for (int kt = 0; kt < nk; ++kt) {
-        const unsigned char *base = lds + (kt & 1) * STAGE;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16 - 1; ++ks) {
-            read_frags(base, (ks + 1) & 1, ks + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_step(ks & 1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (kt + 1 < nk) {
-            __builtin_amdgcn_s_waitcnt(0);   // next slice's loads landed; my last fragments are in registers
-            __syncthreads();                 // ... for every wave: stage (kt & 1) is free, stage (kt+1)&1 is full
-            read_frags(lds + ((kt + 1) & 1) * STAGE, 0, 0);
-            if (kt + 2 < nk) issue(kt & 1, (kt + 2) * BK);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step((BK / 16 - 1) & 1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-
-    // ---- epilogue.  Accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its
-    //      32x32 tile.  Each wave parks its tile as bf16 in its own LDS region, then streams it out in
-    //      16-byte pieces so that every store instruction covers whole 256-byte row segments.
-    __syncthreads();                         // every wave is done reading operand tiles
-    if (!SWIGLU) {
-        bf16_t *ct = reinterpret_cast<bf16_t *>(lds) + (size_t)wave * Cfg::WTM * Cfg::CP;
+    // ---- k slices [kb, ke) of the current tile into acc
+    auto run = [&](int kb, int ke) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * Cfg::CP + j * 32 + lrow] = (bf16_t)acc[i][j][r];
-        // only this wave reads what it wrote: LDS accesses of one wave are ordered, no barrier needed
-        constexpr int CPR = Cfg::WTN / 8;        // 16-byte pieces per row
-        constexpr int PIECES = Cfg::WTM * CPR;
-        const int gm0 = m0 + wm * Cfg::WTM, gn0 = n0 + wn * Cfg::WTN;
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        const int n = ke - kb;
+        if (SK) __syncthreads();   // the previous segment's epilogue may still be reading its LDS staging area
+        issue(0, kb * BK);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        read_frags(lds, 0, 0);
+        if (n > 1) issue(1, (kb + 1) * BK);
+        if (!PIPE) {
+            for (int kt = 0; kt < n; ++kt) {
+                const unsigned char *base = lds + (kt & 1) * STAGE;
 #pragma unroll
-        for (int p = lane; p < PIECES; p += 64) {
-            const int row = p / CPR, cc = (p % CPR) * 8;
-            const int gm = gm0 + row, gn = gn0 + cc;
-            if (gm < M && gn < N)                // N % 8 == 0: a piece is entirely inside or outside
-                *reinterpret_cast<uint4 *>(C + (size_t)gm * N + gn) =
-                    *reinterpret_cast<const uint4 *>(ct + row * Cfg::CP + cc);
-        }
-    } else {
-        constexpr int HW = Cfg::WTN / 2;         // output columns per wave
-        constexpr int HP = HW + 8;               // LDS pitch
-        const int F = N / 2;
-        bf16_t *ct = reinterpret_cast<bf16_t *>(lds) + (size_t)wave * Cfg::WTM * HP;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int jp = 0; jp < TN / 2; ++jp)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float g = acc[i][2 * jp][r], u = acc[i][2 * jp + 1][r];
-                    const float a = g / (1.0f + __expf(-g)) * u;
-                    ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * HP + jp * 32 + lrow] = (bf16_t)a;
+                for (int ks = 0; ks < BK / 16 - 1; ++ks) {
+                    read_frags(base, (ks + 1) & 1, ks + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_step(ks & 1);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-        constexpr int CPR = HW / 8;
-        constexpr int PIECES = Cfg::WTM * CPR;
-        const int gm0 = m0 + wm * Cfg::WTM, gf0 = tile_n * (BN / 2) + wn * HW;
+                if (kt + 1 < n) {
+                    __builtin_amdgcn_s_waitcnt(0);   // next slice's loads landed; my last fragments are in registers
+                    __syncthreads();                 // ... for every wave: stage (kt & 1) is free, the other is full
+                    read_frags(lds + ((kt + 1) & 1) * STAGE, 0, 0);
+                    if (kt + 2 < n) issue(kt & 1, (kb + kt + 2) * BK);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_step((BK / 16 - 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+            // Interleaved schedule: inside every k-step the fragment reads of the next step (and, in the
+            // hand-over step, the direct-to-LDS loads two slices ahead) are slotted between the MFMAs, one
+            // memory instruction per MFMA, so a wave's memory issue runs in the shadow of its own matrix
+            // instructions instead of leaving the matrix pipe idle.
+            constexpr int NMFMA = TM * TN, NREAD = TM + TN, NLOAD = A_LOADS + W_LOADS;
+            auto weave = [&](bool with_loads) {
 #pragma unroll
-        for (int p = lane; p < PIECES; p += 64) {
-            const int row = p / CPR, cc = (p % CPR) * 8;
-            const int gm = gm0 + row, gf = gf0 + cc;
-            if (gm < M && gf < F)                // F % 8 == 0
-                *reinterpret_cast<uint4 *>(C + (size_t)gm * F + gf) =
-                    *reinterpret_cast<const uint4 *>(ct + row * HP + cc);
+                for (int i = 0; i < NREAD; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                }
+                if (with_loads) {
+                    constexpr int REST = NMFMA - NREAD > 0 ? NMFMA - NREAD : 1;
+                    constexpr int PER = (NLOAD + REST - 1) / REST;
+#pragma unroll
+                    for (int i = 0; i < REST; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x020, PER, 0);   // global -> LDS loads
+                    }
+                }
+            };
+            auto slice = [&](int kt, auto handover, auto more) {
+                const unsigned char *base = lds + (kt & 1) * STAGE;
+#pragma unroll
+                for (int ks = 0; ks < BK / 16 - 1; ++ks) {
+                    read_frags(base, (ks + 1) & 1, ks + 1);
+                    mfma_step(ks & 1);
+                    weave(false);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (handover) {
+                    __builtin_amdgcn_s_waitcnt(0);   // next slice's loads landed; my last fragments are in registers
+                    __syncthreads();                 // ... for every wave: stage (kt & 1) is free, the other is full
+                    read_frags(lds + ((kt + 1) & 1) * STAGE, 0, 0);
+                    if (more) issue(kt & 1, (kb + kt + 2) * BK);
+                }
+                mfma_step((BK / 16 - 1) & 1);
+                if (handover) weave(more);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            for (int kt = 0; kt < n - 2; ++kt) slice(kt, std::true_type{}, std::true_type{});
+            if (n >= 2) slice(n - 2, std::true_type{}, std::false_type{});
+            slice(n - 1, std::false_type{}, std::false_type{});
+        }
+    };
+
+    // ---- epilogue.  Accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its
+    //      32x32 tile.  Each wave parks its tile as bf16 in its own LDS region, then streams it out in
+    //      16-byte pieces so that every store instruction covers whole 256-byte row segments.
+    auto store_tile = [&]() {
+        __syncthreads();                         // every wave is done reading operand tiles
+        if (!SWIGLU) {
+            bf16_t *ct = reinterpret_cast<bf16_t *>(lds) + (size_t)wave * Cfg::WTM * Cfg::CP;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * Cfg::CP + j * 32 + lrow] =
+                            (bf16_t)acc[i][j][r];
+            // only this wave reads what it wrote: LDS accesses of one wave are ordered, no barrier needed
+            constexpr int CPR = Cfg::WTN / 8;        // 16-byte pieces per row
+            constexpr int PIECES = Cfg::WTM * CPR;
+            const int gm0 = m0 + wm * Cfg::WTM, gn0 = n0 + wn * Cfg::WTN;
+#pragma unroll
+            for (int p = lane; p < PIECES; p += 64) {
+                const int row = p / CPR, cc = (p % CPR) * 8;
+                const int gm = gm0 + row, gn = gn0 + cc;
+                if (gm < M && gn < N)                // N % 8 == 0: a piece is entirely inside or outside
+                    *reinterpret_cast<uint4 *>(C + (size_t)gm * N + gn) =
+                        *reinterpret_cast<const uint4 *>(ct + row * Cfg::CP + cc);
+            }
+        } else {
+            constexpr int HW = Cfg::WTN / 2;         // output columns per wave
+            constexpr int HP = HW + 8;               // LDS pitch
+            const int F = N / 2;
+            bf16_t *ct = reinterpret_cast<bf16_t *>(lds) + (size_t)wave * Cfg::WTM * HP;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int jp = 0; jp < TN / 2; ++jp)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float g = acc[i][2 * jp][r], u = acc[i][2 * jp + 1][r];
+                        const float a = g / (1.0f + __expf(-g)) * u;
+                        ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * HP + jp * 32 + lrow] = (bf16_t)a;
+                    }
+            constexpr int CPR = HW / 8;
+            constexpr int PIECES = Cfg::WTM * CPR;
+            const int gm0 = m0 + wm * Cfg::WTM, gf0 = tile_n * (BN / 2) + wn * HW;
+#pragma unroll
+            for (int p = lane; p < PIECES; p += 64) {
+                const int row = p / CPR, cc = (p % CPR) * 8;
+                const int gm = gm0 + row, gf = gf0 + cc;
+                if (gm < M && gf < F)                // F % 8 == 0
+                    *reinterpret_cast<uint4 *>(C + (size_t)gm * F + gf) =
+                        *reinterpret_cast<const uint4 *>(ct + row * HP + cc);
+            }
+        }
+    };
+
+    if (!SK) {
+        // workgroup -> tile: contiguous tile range per XCD (workgroup ids go round-robin over the 8 XCDs),
+        // groups of 8 tile rows, tile row fastest inside a group (neighbours share the W tile)
+        int pid = blockIdx.x;
+        const int per_xcd = nt / 8;
+        if (pid < per_xcd * 8) pid = (pid % 8) * per_xcd + pid / 8;
+        constexpr int GROUP = 8;
+        const int width = GROUP * tiles_n;
+        const int first_m = (pid / width) * GROUP;
+        const int gsize = min(tiles_m - first_m, GROUP);
+        set_tile(first_m + (pid % width) % gsize, (pid % width) / gsize);
+        run(0, nk);
+        store_tile();
+    } else {
+        // Teams of TS workgroups: member r of a team owns tile row gm*TS + r of the team's current column
+        // (gm, tile_n), and all members walk the same k range, so the W slices they fetch are shared in L2.
+        // The (column, k-slice) units are dealt to the teams in equal contiguous spans.
+        const int TS = sk_team, bid = blockIdx.x;
+        const int GT = gridDim.x / TS;
+        int q, r;                                // team, member
+        const int tpx = GT >> 3;                 // teams per XCD (grouped mapping)
+        if (sk_grouped) {                        // team members and neighbouring teams share an XCD
+            const int idx = bid >> 3;
+            q = (bid & 7) * tpx + idx / TS;
+            r = idx % TS;
+        } else {
+            q = bid / TS;
+            r = bid % TS;
+        }
+        auto wg_of = [&](int qq) { return sk_grouped ? ((qq % tpx) * TS + r) * 8 + qq / tpx : qq * TS + r; };
+        const int ngm = (tiles_m + TS - 1) / TS;
+        const long long U = (long long)ngm * tiles_n * nk;
+        auto span_begin = [&](int j) { return (int)(U * j / GT); };
+        const int u0 = span_begin(q), u1 = span_begin(q + 1);
+        unsigned *flags = reinterpret_cast<unsigned *>(sk_ws);
+        const __amdgpu_buffer_rsrc_t rs_p = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(sk_ws + SK_HDR), 0, (int)((uint32_t)gridDim.x * (uint32_t)Cfg::SLOT_BYTES), 0x00020000);
+        // column -> (tile row of this member, tile column); false if the member has no tile row there
+        auto set_col = [&](int col) {
+            const int tm = (col / tiles_n) * TS + r;
+            if (tm < tiles_m) set_tile(tm, col % tiles_n);
+            return tm < tiles_m;
+        };
+
+        int owner_end = u1;
+        if (u1 % nk != 0) {                      // the span stops inside a column: partial segment, done first
+            const int col = u1 / nk;
+            const int kb = max(u0, col * nk) - col * nk, ke = u1 - col * nk;
+            if (set_col(col)) {
+                run(kb, ke);
+                // Partials and flags bypass the per-XCD L2 caches in both directions (system-scope loads and
+                // stores), so the hand-over needs no cache write-back or invalidate, which would evict the
+                // operand tiles of every workgroup on the XCD.
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int v4 = 0; v4 < 4; ++v4) {
+                            f32x4_t v = {acc[i][j][4 * v4], acc[i][j][4 * v4 + 1], acc[i][j][4 * v4 + 2],
+                                         acc[i][j][4 * v4 + 3]};
+                            __builtin_amdgcn_raw_buffer_store_b128(
+                                __builtin_bit_cast(u32x4_t, v), rs_p,
+                                (uint32_t)(bid * (int)Cfg::SLOT_BYTES +
+                                           (((i * TN + j) * 4 + v4) * Cfg::NT + tid) * 16),
+                                0, SK_COHERENT);
+                        }
+                __builtin_amdgcn_s_waitcnt(0);   // my stores have reached memory ...
+                __syncthreads();                 // ... and so have everybody's, before the flag goes up
+                if (tid == 0)
+                    __hip_atomic_store(&flags[bid], sk_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+            owner_end = col * nk;
+        }
+        // Finishing segments.  The one that starts inside a column depends on the partial of lower teams, which
+        // can be almost a whole column long: it goes last, after the columns that start in this span.
+        const int head_col = u0 / nk, head_kb = u0 - head_col * nk;
+        const int first_full = head_kb ? head_col + 1 : head_col;
+        const int n_full = max(0, owner_end / nk - first_full);
+        const int n_own = n_full + ((head_kb && (head_col + 1) * nk <= owner_end) ? 1 : 0);
+        for (int o = 0; o < n_own; ++o) {
+            const int col = o < n_full ? first_full + o : head_col;
+            const int kb = o < n_full ? 0 : head_kb;
+            if (!set_col(col)) continue;
+            run(kb, nk);
+            if (kb > 0) {                        // lower teams hold the first kb slices of this column
+                int qfirst = q - 1;
+                while (qfirst > 0 && span_begin(qfirst) > col * nk) --qfirst;
+                if (tid == 0) {
+                    for (int j = qfirst; j < q; ++j) {
+                        unsigned spins = 0;
+                        while (__hip_atomic_load(&flags[wg_of(j)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) !=
+                               sk_epoch) {
+                            __builtin_amdgcn_s_sleep(32);
+                            if (++spins > SK_SPIN_LIMIT) {
+                                __hip_atomic_store(sk_err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                                break;
+                            }
+                        }
+                    }
+                }
+                __syncthreads();
+                for (int j = qfirst; j < q; ++j) {
+                    const int src = wg_of(j);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int jj = 0; jj < TN; ++jj)
+#pragma unroll
+                            for (int v4 = 0; v4 < 4; ++v4) {
+                                const f32x4_t v = __builtin_bit_cast(
+                                    f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                 rs_p,
+                                                 (uint32_t)(src * (int)Cfg::SLOT_BYTES +
+                                                            (((i * TN + jj) * 4 + v4) * Cfg::NT + tid) * 16),
+                                                 0, SK_COHERENT));
+                                acc[i][jj][4 * v4] += v[0];
+                                acc[i][jj][4 * v4 + 1] += v[1];
+                                acc[i][jj][4 * v4 + 2] += v[2];
+                                acc[i][jj][4 * v4 + 3] += v[3];
+                            }
+                }
+            }
+            store_tile();
         }
     }
 #endif
 }
 
-template <int BM, int BN, int WM, int WN, int SWZ, bool SWIGLU>
+template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE>
 hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     using Cfg = DtlCfg<BM, BN, WM, WN>;
     static bool attr_set = false;
-    auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWZ, SWIGLU>;
+    auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWIGLU, PIPE, false>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
@@ -256,11 +443,61 @@ hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hi
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     dim3 grid(tiles_m * tiles_n), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
-                       K, tiles_m, tiles_n);
+                       K, tiles_m, tiles_n, (unsigned char *)nullptr, 0u, (unsigned *)nullptr, 1, 0);
+    return hipGetLastError();
+}
+
+// Stream-K launch shape.  Team size: the largest power of two (at most 8) that tiles the tile rows without idle
+// members; the grouped mapping needs 8 * TS to divide the grid and every team a non-empty span, otherwise teams
+// of one in launch order.  Returns the k-slices each team gets.
+long long sk_plan(int M, int N, int K, int num_wg, int *TS_, int *G_, int *grouped_) {
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256, nk = K / BK;
+    int TS = 1;
+    for (int t = 2; t <= 8; t *= 2)
+        if (tiles_m % t == 0) TS = t;
+#ifdef ISO_EXP_TS
+    if (getenv("ISO_SK_TS")) TS = atoi(getenv("ISO_SK_TS"));
+#endif
+    int G = (num_wg / (8 * TS)) * 8 * TS, grouped = 1;
+    long long units = (long long)(tiles_m / TS) * tiles_n * nk;
+    if (G < 8 * TS || units < G / TS) {   // tiny problem or odd device
+        TS = 1;
+        grouped = 0;
+        units = (long long)tiles_m * tiles_n * nk;
+        G = units < num_wg ? (int)units : num_wg;
+    }
+    *TS_ = TS;
+    *G_ = G;
+    *grouped_ = grouped;
+    return units / (G / TS);
+}
+
+// stream-K launch of the 256x256 tile: one workgroup per compute unit
+template <bool SWIGLU>
+hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K, iso_sk_ws *sk, hipStream_t s) {
+    using Cfg = DtlCfg<256, 256, 4, 2>;
+    static bool attr_set = false;
+    auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, SWIGLU, true, true>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    int TS, G, grouped;
+    sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped);
+    ++sk->epoch;
+    dim3 grid(G), block(Cfg::NT);
+    hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
+                       K, tiles_m, tiles_n, (unsigned char *)sk->base, sk->epoch, sk->err, TS, grouped);
     return hipGetLastError();
 }
 
 }  // namespace
+
+size_t iso_gemm_sk_ws_bytes(int num_wg) { return SK_HDR + (size_t)num_wg * DtlCfg<256, 256, 4, 2>::SLOT_BYTES; }
+int iso_gemm_sk_max_wg(void) { return SK_MAX_WG; }
 
 bool iso_gemm_bf16_dtl_supported(int M, int N, int K) {
     return M >= 1 && N >= 8 && (N % 8) == 0 && K >= BK && (K % BK) == 0 && (long long)M * K < (1ll << 31) &&
@@ -276,21 +513,32 @@ static int pick_variant(int M, int N) {
     return tiles_256 >= 128 ? 1 : 3;
 }
 
+// Stream-K or one tile per workgroup?  Measured over the same shapes: with at least ~40 k-slices per team the
+// stream-K launch wins (every compute unit busy whatever the tile count, and team members share their W slices in
+// L2); with less k depth the cost of parking and fetching the partial tiles (about 13 us per workgroup) dominates.
+static bool sk_wanted(int M, int N, int K, const iso_sk_ws *sk) {
+    if (!sk || !sk->base || sk->num_wg < 8) return false;
+    int TS, G, grouped;
+    return sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped) >= 40 && grouped;
+}
+
 // variant: 0 = pick by shape; 1 = 256x256 8 waves, 2 = 256x128 8 waves, 3 = 128x128 4 waves, 4 = 128x256 8 waves,
-//          5 = 256x256 4 waves; +8 selects the other LDS swizzle
+//          5 = 256x256 4 waves, 6 = 256x256 stream-K; +8 selects the plain (non-interleaved) main loop.
+// sk may be null: then the stream-K kernel is not considered (variant 6 is an error).
 hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M, int N, int K, int variant,
-                                    hipStream_t s) {
+                                    iso_sk_ws *sk, hipStream_t s) {
     int v = variant & 7;
-    const int sw = (variant >> 3) & 1;
-    if (v == 0) v = pick_variant(M, N);
-#define ISO_DTL(BM_, BN_, WM_, WN_)                                                          \
-    return sw ? launch<BM_, BN_, WM_, WN_, 0, false>(a, w, c, M, N, K, s)                    \
-              : launch<BM_, BN_, WM_, WN_, 1, false>(a, w, c, M, N, K, s)
+    const int plain = (variant >> 3) & 1;
+    if (v == 0) v = sk_wanted(M, N, K, sk) ? 6 : pick_variant(M, N);
+#define ISO_DTL(BM_, BN_, WM_, WN_)                                                       \
+    return plain ? launch<BM_, BN_, WM_, WN_, false, false>(a, w, c, M, N, K, s)          \
+                 : launch<BM_, BN_, WM_, WN_, false, true>(a, w, c, M, N, K, s)
     switch (v) {
         case 1: ISO_DTL(256, 256, 4, 2);
         case 2: ISO_DTL(256, 128, 4, 2);
         case 4: ISO_DTL(128, 256, 2, 4);
         case 5: ISO_DTL(256, 256, 2, 2);
+        case 6: return (sk && sk->base) ? launch_sk<false>(a, w, c, M, N, K, sk, s) : hipErrorInvalidValue;
         default: ISO_DTL(128, 128, 2, 2);
     }
 #undef ISO_DTL
@@ -302,13 +550,14 @@ bool iso_gemm_swiglu_bf16_supported(int M, int F, int K) {
 }
 
 hipError_t iso_launch_gemm_swiglu_bf16(const void *a, const void *w, void *act, int M, int F, int K, int variant,
-                                       hipStream_t s) {
+                                       iso_sk_ws *sk, hipStream_t s) {
     int v = variant & 7;
-    if (v == 0) v = pick_variant(M, 2 * F);
+    if (v == 0) v = sk_wanted(M, 2 * F, K, sk) ? 6 : pick_variant(M, 2 * F);
     switch (v) {
-        case 1: return launch<256, 256, 4, 2, 1, true>(a, w, act, M, 2 * F, K, s);
-        case 2: return launch<256, 128, 4, 2, 1, true>(a, w, act, M, 2 * F, K, s);
-        case 4: return launch<128, 256, 2, 4, 1, true>(a, w, act, M, 2 * F, K, s);
-        default: return launch<128, 128, 2, 2, 1, true>(a, w, act, M, 2 * F, K, s);
+        case 1: return launch<256, 256, 4, 2, true, true>(a, w, act, M, 2 * F, K, s);
+        case 2: return launch<256, 128, 4, 2, true, true>(a, w, act, M, 2 * F, K, s);
+        case 4: return launch<128, 256, 2, 4, true, true>(a, w, act, M, 2 * F, K, s);
+        case 6: return (sk && sk->base) ? launch_sk<true>(a, w, act, M, 2 * F, K, sk, s) : hipErrorInvalidValue;
+        default: return launch<128, 128, 2, 2, true, true>(a, w, act, M, 2 * F, K, s);
     }
 }

@@ -98,12 +98,21 @@ struct Timed {
 inline char *at(void *base, size_t row, size_t width, size_t e) { return (char *)base + row * width * e; }
 inline const char *at(const void *base, size_t row, size_t width, size_t e) { return (const char *)base + row * width * e; }
 
+// Stream-K workspace for a launch on stream s: the context owns one per stream of its own, so launches that share
+// a workspace are ordered; a foreign stream gets none and takes the plain kernels.
+iso_sk_ws *sk_for(iso_ctx *ctx, hipStream_t s) {
+    if (((ctx->flags & ISO_FLAG_NO_STREAMK) || ctx->sk_hold) && ((ctx->flags >> 8) & 7) != 6) return nullptr;
+    if (s == ctx->stream[0] && ctx->sk[0].base) return &ctx->sk[0];
+    if (s == ctx->stream[1] && ctx->sk[1].base) return &ctx->sk[1];
+    return nullptr;
+}
+
 int gemm(iso_ctx *ctx, int kind, const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     Timed t_(ctx, kind, s);
     hipError_t e;
     const bool mfma = ctx->cfg.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_GEMM);
     if (mfma && !(ctx->flags & ISO_FLAG_GEMM_STAGED) && iso_gemm_bf16_dtl_supported(M, N, K))
-        e = iso_launch_gemm_bf16_dtl(a, w, c, M, N, K, (ctx->flags >> 8) & 15, s);
+        e = iso_launch_gemm_bf16_dtl(a, w, c, M, N, K, (ctx->flags >> 8) & 15, sk_for(ctx, s), s);
     else if (mfma && iso_gemm_bf16_mfma_supported(M, N, K))
         e = iso_launch_gemm_bf16_mfma(a, w, c, M, N, K, s);
     else
@@ -218,7 +227,7 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
                        iso_gemm_swiglu_bf16_supported(ck.n, F, H);
     if (fused) {   // gate/up projection with the activation in its epilogue: the [Tc, 2F] tensor never exists
         Timed t_(ctx, ISO_K_GEMM_GATE_UP, ck.s);
-        hipError_t e_ = iso_launch_gemm_swiglu_bf16(yr, w->w_gate_up, actr, ck.n, F, H, (ctx->flags >> 8) & 15, ck.s);
+        hipError_t e_ = iso_launch_gemm_swiglu_bf16(yr, w->w_gate_up, actr, ck.n, F, H, (ctx->flags >> 8) & 15, sk_for(ctx, ck.s), ck.s);
         if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "gate/up+swiglu launch: %s", hipGetErrorString(e_));
     } else {
         ISO_TRY(gemm(ctx, ISO_K_GEMM_GATE_UP, yr, w->w_gate_up, gur, ck.n, 2 * F, H, ck.s));
@@ -267,6 +276,14 @@ int run_stack(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, vo
     Chunk ch[2] = {{0, two ? split : T, s0}, {split, T - split, s1}};
     const int nc = two ? 2 : 1;
 
+    // Stream-K takes every compute unit for one GEMM.  That pays while the other chunk's stream mostly waits for
+    // its bf16 transfers; when two chunks compute side by side most of the time (no transfers, or the halved int8
+    // ones) the tile-per-workgroup launches share the chip better (measured: 4-7 % either way).
+    struct SkHold {
+        iso_ctx *c;
+        ~SkHold() { c->sk_hold = 0; }
+    } sk_hold_{ctx};
+    ctx->sk_hold = overlap && comm != ISO_COMM_D2H;
     if (overlap) {   // fork: stream1 starts after whatever produced x in stream0
         HIP_TRY(hipEventRecord(ctx->ev_fork, s0));
         HIP_TRY(hipStreamWaitEvent(s1, ctx->ev_fork, 0));
@@ -374,6 +391,24 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
         }
         if (!hip_ok(hipHostMalloc(&ctx->host_sink, 2 * (size_t)cfg->max_seq * cfg->hidden * ctx->elt, hipHostMallocDefault),
                     "hipHostMalloc(sink)")) break;
+        if (cfg->dtype == ISO_BF16) {   // stream-K GEMM workspaces: one per stream, one shared error word
+            int cus = 0;
+            if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev), "device attribute")) break;
+            if (cus > iso_gemm_sk_max_wg()) cus = iso_gemm_sk_max_wg();
+            unsigned *err = nullptr;
+            if (!hip_ok(hipHostMalloc((void **)&err, 64, hipHostMallocDefault), "hipHostMalloc(stream-K status)")) break;
+            *err = 0;
+            ctx->sk[0].err = ctx->sk[1].err = err;
+            const size_t bytes = iso_gemm_sk_ws_bytes(cus);
+            bool ok = true;
+            for (int i = 0; i < 2 && ok; ++i) {
+                ctx->sk[i].num_wg = cus;
+                ctx->sk[i].epoch = 0;
+                ok = hip_ok(hipMalloc(&ctx->sk[i].base, bytes), "hipMalloc(stream-K workspace)") &&
+                     hip_ok(hipMemset(ctx->sk[i].base, 0, 4096), "hipMemset(stream-K flags)");
+            }
+            if (!ok) break;
+        }
         if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming), "event")) break;
         if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming), "event")) break;
         if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_kv0, hipEventDisableTiming), "event")) break;
@@ -393,6 +428,10 @@ int iso_sync(iso_ctx *ctx) {
     if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
     HIP_TRY(hipStreamSynchronize(ctx->stream[0]));
     if (ctx->stream[1] != ctx->stream[0]) HIP_TRY(hipStreamSynchronize(ctx->stream[1]));
+    if (ctx->sk[0].err && *ctx->sk[0].err) {
+        *ctx->sk[0].err = 0;
+        return fail(ISO_ERR_HIP, "stream-K GEMM: a wait for a partial tile ran out; results of this pass are invalid");
+    }
     return ISO_OK;
 }
 
@@ -412,6 +451,9 @@ int iso_destroy(iso_ctx *ctx) {
     if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
     if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
     if (ctx->ev_kv0) (void)hipEventDestroy(ctx->ev_kv0);
+    if (ctx->sk[0].err) (void)hipHostFree(ctx->sk[0].err);
+    for (int i = 0; i < 2; ++i)
+        if (ctx->sk[i].base) (void)hipFree(ctx->sk[i].base);
     if (ctx->host_sink) (void)hipHostFree(ctx->host_sink);
     if (ctx->rope_cos) (void)hipFree(ctx->rope_cos);
     if (ctx->rope_sin) (void)hipFree(ctx->rope_sin);

@@ -11,7 +11,17 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// Workspace of one stream-K GEMM in flight (flag words + one fp32 partial tile per workgroup).  Launches that
+// share a workspace must be ordered (same stream); the context keeps one per stream of its own.
+struct iso_sk_ws {
+    void *base;        // device; flag words zeroed once at creation, never reset (each launch uses a new epoch)
+    unsigned *err;     // pinned host word the kernel sets if a bounded wait ran out
+    unsigned epoch;    // launch counter
+    int num_wg;        // grid size = compute units of the device
+};
 
 struct iso_ctx {
     iso_cfg cfg;
@@ -33,6 +43,8 @@ struct iso_ctx {
     float *x1f;        // [max_seq, hidden] fp32: residual stream between the two blocks of a bf16 layer
     float *rope_cos;   // [max_seq, d/2]
     float *rope_sin;   // [max_seq, d/2]
+    int sk_hold;       // set while a pass enqueues work for which stream-K is not to be picked
+    iso_sk_ws sk[2];   // stream-K GEMM workspaces, one per stream (bf16 contexts only; base == null otherwise)
     void *host_sink;   // pinned, 2 * max_seq * hidden elements
     // optional per-launch timing (iso_timing_*): event pairs recorded around every launch, in its stream
     int timing;
@@ -55,10 +67,12 @@ hipError_t iso_launch_gemm_simple(int dtype, const void *a, const void *w, void 
 hipError_t iso_launch_gemm_bf16_mfma(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s);
 bool iso_gemm_bf16_mfma_supported(int M, int N, int K);
 hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M, int N, int K, int variant,
-                                    hipStream_t s);
+                                    iso_sk_ws *sk_or_null, hipStream_t s);
 bool iso_gemm_bf16_dtl_supported(int M, int N, int K);
 hipError_t iso_launch_gemm_swiglu_bf16(const void *a, const void *w, void *act, int M, int F, int K, int variant,
-                                       hipStream_t s);
+                                       iso_sk_ws *sk_or_null, hipStream_t s);
+size_t iso_gemm_sk_ws_bytes(int num_wg);   // device bytes a stream-K workspace for num_wg workgroups needs
+int iso_gemm_sk_max_wg(void);
 bool iso_gemm_swiglu_bf16_supported(int M, int F, int K);
 hipError_t iso_launch_attn_simple(int dtype, const void *q, const void *k, const void *v, void *out, int Tc,
                                   int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);

@@ -115,7 +115,8 @@ GEMM_SHAPES = [(1, 8, 8), (64, 128, 64), (128, 128, 64), (129, 130, 72), (300, 2
 
 @pytest.mark.parametrize("dt,flags", [("f32", 0), ("bf16", 0), ("bf16", iso.ISO_FLAG_GEMM_STAGED),
                                       ("bf16", iso.ISO_FLAG_SIMPLE_GEMM),
-                                      ("bf16", 1 << 8), ("bf16", 2 << 8), ("bf16", 4 << 8), ("bf16", 5 << 8)])
+                                      ("bf16", 1 << 8), ("bf16", 2 << 8), ("bf16", 3 << 8), ("bf16", 4 << 8),
+                                      ("bf16", 5 << 8), ("bf16", 6 << 8), ("bf16", 9 << 8)])
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
 def test_gemm_rowpar(dt, flags, M, N, K):
     a = iso_inputs.randn((M, K), seed=M + N + K, dtype=dt)
@@ -131,6 +132,29 @@ def test_gemm_rowpar(dt, flags, M, N, K):
         assert orc.max_rel_err(f64(c), ref) <= TOL_STEP[dt]
         np.testing.assert_array_equal(sink.array, c.numpy())   # the communication stand-in moved exactly the partial
         sink.free()
+
+
+def test_gemm_stream_k_repeated_launches_and_both_streams():
+    """The stream-K kernel hands partial tiles between workgroups through a workspace whose flags are never
+    reset (each launch has its own epoch): launches in a row, with changing shapes and on both streams of the
+    context at once, must each match the oracle and the plain 256x256 kernel bit for bit in nothing but sum order
+    (compared through the oracle, not to each other)."""
+    dt = "bf16"
+    with make_ctx(256, 4, 4, 64, 64, dt, 256) as ctx:
+        ctx.set_flags(6 << 8)
+        cases = [(700, 1000, 4096), (513, 1280, 2048), (256, 256, 64), (1024, 2304, 1664), (300, 520, 8192),
+                 (700, 1000, 4096)]
+        outs = []
+        for i, (M, N, K) in enumerate(cases):
+            a = iso_inputs.randn((M, K), seed=100 + i, dtype=dt)
+            w = iso_inputs.randn((N, K), seed=200 + i, dtype=dt, scale=K ** -0.5)
+            c = iso.DeviceArray((M, N), dt, fill_byte=NAN_BYTE)
+            stream = ctx.stream0 if i % 2 == 0 else ctx.stream1
+            ctx.gemm_rowpar(dev(a, dt), dev(w, dt), c, M, N, K, stream)
+            outs.append((a, w, c))
+        ctx.sync()
+        for a, w, c in outs:
+            assert orc.max_rel_err(f64(c), orc.linear(h64(a, dt), h64(w, dt))) <= TOL_STEP[dt]
 
 
 def test_gemm_rejects_bad_shapes():
@@ -254,7 +278,7 @@ def test_comm_stand_in_delivers_both_partials_to_the_host():
 
 
 @pytest.mark.parametrize("flags", [0, iso.ISO_FLAG_SIMPLE_GEMM | iso.ISO_FLAG_SIMPLE_ATTN, iso.ISO_FLAG_GEMM_STAGED,
-                                   iso.ISO_FLAG_NO_FUSE, 1 << 8, 2 << 8, 3 << 8, 4 << 8])
+                                   iso.ISO_FLAG_NO_FUSE, 1 << 8, 2 << 8, 3 << 8, 4 << 8, 6 << 8])
 @pytest.mark.parametrize("hidden,nq,nkv,ffn,T,splits", [
     (512, 4, 1, 768, 300, (0, 130, 299)),       # GQA, ragged everything
     (384, 3, 3, 200, 257, (128, 1)),            # MHA, odd head count
