@@ -57,7 +57,9 @@ typedef enum {
 /* How the two chunks are issued (Section 1, Figure 1 (a) versus (d)). */
 typedef enum {
     ISO_SCHED_OVERLAP = 0, /* chunk 0 on stream0, chunk 1 on stream1, one event: KV of chunk 0 written */
-    ISO_SCHED_SERIAL = 1   /* both chunks on stream0, one block after the other, copies in line        */
+    ISO_SCHED_SERIAL = 1,  /* every chunk on stream0, one block after the other, copies in line        */
+    ISO_SCHED_STREAM_PER_CHUNK = 2 /* each chunk on a stream of its own (the context makes the extra ones), attention
+                                      blocks chained in chunk order; meant for more than two chunks            */
 } iso_sched;
 
 typedef struct {
@@ -94,6 +96,8 @@ typedef struct {
     size_t workspace_bytes;   /* device workspace a context for cfg.max_seq holds   */
 } iso_plan;
 
+#define ISO_MAX_CHUNKS 8      /* most chunks one prompt may be cut into */
+
 /* Checks a configuration; returns ISO_OK or the error iso_create would return for it.  Host only. */
 int iso_validate_cfg(const iso_cfg *cfg);
 
@@ -102,6 +106,16 @@ int iso_validate_cfg(const iso_cfg *cfg);
  * chunk.  Host only.  Errors: NULL, bad cfg, T < 1, T > max_seq (ISO_ERR_WORKSPACE), split outside
  * [0, T] (ISO_ERR_SPLIT). */
 int iso_plan_chunks(const iso_cfg *cfg, int T, int split, iso_plan *out);
+
+/* Cut points for n_chunks chunks of equal estimated cost instead of equal length (Section 6: the later part of
+ * the sequence is dearer, so the first chunk should be longer; finer cuts than two).  The cost of position i is
+ * the layer's projection flops per token plus attn_flop_cost * 4 * nq * d * (i + 1) for its attention over
+ * i + 1 keys; attn_flop_cost says how much dearer an attention flop is than a projection flop on the machine
+ * (<= 0 selects 3.0, the ratio measured on MI355X at these shapes).  bounds[0 .. n_chunks-2] receives the
+ * ascending cut points, each a multiple of 128 when T >= 256 * n_chunks.  Host only.
+ * Errors: NULL, bad cfg, T < 1 or n_chunks outside [1, min(T, ISO_MAX_CHUNKS)] (ISO_ERR_SHAPE),
+ * T > max_seq (ISO_ERR_WORKSPACE). */
+int iso_plan_split(const iso_cfg *cfg, int T, int n_chunks, double attn_flop_cost, int *bounds);
 
 /* Creates a context on the current HIP device: workspace for max_seq tokens, the rotary table
  * (computed on the host in double, stored fp32), one event pair, and pinned host memory for the
@@ -132,6 +146,19 @@ int iso_layer_prefill(iso_ctx *ctx, const iso_weights *w, void *x, void *k_cache
  * of layer l overlaps the attention block of layer l+1 of the other chunk. */
 int iso_stack_prefill(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x,
                       void *k_caches, void *v_caches, int T, int split, int comm, int sched);
+
+/* The same stack with the prompt cut into n_chunks chunks at bounds[0] < bounds[1] < ... (Section 6: finer
+ * segmentation than two chunks; the figure that draws it is not available, this is the natural extension of the
+ * two-chunk schedule).  Chunk c covers [bounds[c-1], bounds[c]) with bounds[-1] = 0 and bounds[n_chunks-1] = T,
+ * runs on stream c % 2 in ISO_SCHED_OVERLAP (all on stream0 in ISO_SCHED_SERIAL), and its attention waits for
+ * the K/V rows of chunk c-1 (hence of every earlier chunk).  More chunks shorten the two ends of the pipeline
+ * that nothing overlaps (the first attention block and the last transfer) at the price of smaller GEMMs.
+ * n_chunks == 1 ignores bounds (may be NULL).  n_chunks == 2 with bounds[0] == split is iso_stack_prefill.
+ * Errors: as iso_stack_prefill; n_chunks outside [1, ISO_MAX_CHUNKS] (ISO_ERR_SHAPE); bounds NULL for
+ * n_chunks > 1 (ISO_ERR_NULL); bounds not strictly ascending inside (0, T) (ISO_ERR_SPLIT). */
+int iso_stack_prefill_chunks(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x,
+                             void *k_caches, void *v_caches, int T, const int *bounds, int n_chunks,
+                             int comm, int sched);
 
 /* Attention of one chunk over the KV cache (Section 3.1; chunked prefill, Section 2.1).
  * q        [Tc, nq, d] device, rotary embedding already applied.

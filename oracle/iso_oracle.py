@@ -202,21 +202,24 @@ def layer_unsplit(x, w: Dict[str, np.ndarray], sh: LayerShape, quant: bool = Fal
     return {"x_out": _mlp_block(x1, w, sh, quant), "k_cache": k, "v_cache": v, "x1": x1, "attn": o, "pa": pa}
 
 
-def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split: int, quant: bool = False) -> Dict[str, np.ndarray]:
-    """The same layer as two chunks [0,split) and [split,T) (Section 3.1).
+def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split, quant: bool = False) -> Dict[str, np.ndarray]:
+    """The same layer as consecutive chunks (Section 3.1: two chunks; Section 6: finer cuts).
 
-    Chunk 0 writes its K/V rows into the cache and attends to them; chunk 1 then
-    writes its rows and attends to the whole cache.  Everything else is per token.
+    `split` is one cut point or an ascending list of cut points strictly inside the prompt.  Chunk c
+    writes its K/V rows into the cache and attends to the cache up to its own last row; everything
+    else is per token.
     """
     x = _f64(x)
     T = x.shape[0]
-    if not 0 < split < T:
-        raise ValueError("split must lie strictly inside the prompt")
+    cuts = [int(split)] if np.isscalar(split) else [int(c) for c in split]
+    edges = [0] + cuts + [T]
+    if any(b <= a for a, b in zip(edges[:-1], edges[1:])):
+        raise ValueError("cut points must be ascending and lie strictly inside the prompt")
     k_cache = np.zeros((T, sh.n_kv_heads, sh.head_dim))
     v_cache = np.zeros((T, sh.n_kv_heads, sh.head_dim))
     x_out = np.empty_like(x)
     x1_all = np.empty_like(x)
-    for lo, hi in ((0, split), (split, T)):
+    for lo, hi in zip(edges[:-1], edges[1:]):
         xc = x[lo:hi]
         pos = np.arange(lo, hi)
         y = rmsnorm(xc, w["g_attn"], sh.rms_eps)
@@ -230,6 +233,29 @@ def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split: int, quant: bo
         x1_all[lo:hi] = x1
         x_out[lo:hi] = _mlp_block(x1, w, sh, quant)
     return {"x_out": x_out, "k_cache": k_cache, "v_cache": v_cache, "x1": x1_all}
+
+
+def token_cost(sh: LayerShape, T: int, attn_flop_cost: float) -> np.ndarray:
+    """Cost of each prompt position in projection-flop units (Section 6: the later half of the
+    sequence is dearer because its attention reads more keys).
+
+    Position i pays the projections (the same for every token) plus attention over i + 1 keys, two
+    products of 2 * d flops per query head and key, weighted by how much dearer an attention flop is
+    than a projection flop.
+    """
+    nq, nkv, d, H, F = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.hidden, sh.ffn
+    proj = 2.0 * H * (nq + 2 * nkv) * d + 2.0 * H * nq * d + 6.0 * H * F
+    keys = np.arange(1, T + 1, dtype=np.float64)
+    return proj + attn_flop_cost * 4.0 * nq * d * keys
+
+
+def balanced_cuts(sh: LayerShape, T: int, n_chunks: int, attn_flop_cost: float) -> np.ndarray:
+    """Real-valued cut positions t_j (j = 1 .. n_chunks-1) at which the cumulative cost of the prompt,
+    taken as a continuous function of the position, reaches j / n_chunks of its total: chunks of
+    equal cost instead of equal length (Section 6)."""
+    c = np.concatenate([[0.0], np.cumsum(token_cost(sh, T, attn_flop_cost))])
+    targets = c[-1] * np.arange(1, n_chunks) / n_chunks
+    return np.interp(targets, c, np.arange(T + 1, dtype=np.float64))
 
 
 def layer_rows(x, w: Dict[str, np.ndarray], sh: LayerShape, rows: Sequence[int], quant: bool = False) -> Dict[str, np.ndarray]:

@@ -15,7 +15,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Dict, Optional, Sequence
+from typing import List, Dict, Optional, Sequence
 
 import numpy as np
 
@@ -25,12 +25,13 @@ ISO_OK = 0
 ISO_ERR_NULL, ISO_ERR_SHAPE, ISO_ERR_DTYPE, ISO_ERR_SPLIT, ISO_ERR_WORKSPACE, ISO_ERR_HIP = -1, -2, -3, -4, -5, -6
 ISO_F32, ISO_BF16 = 0, 1
 ISO_COMM_NONE, ISO_COMM_D2H, ISO_COMM_D2H_INT8 = 0, 1, 2
-ISO_SCHED_OVERLAP, ISO_SCHED_SERIAL = 0, 1
+ISO_SCHED_OVERLAP, ISO_SCHED_SERIAL, ISO_SCHED_STREAM_PER_CHUNK = 0, 1, 2
+ISO_MAX_CHUNKS = 8
 ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN, ISO_FLAG_GEMM_STAGED, ISO_FLAG_NO_FUSE, ISO_FLAG_ATTN_STAGED = 1, 2, 4, 8, 16
 ISO_FLAG_NO_STREAMK = 32
 
 EXPORTS = [
-    "iso_validate_cfg", "iso_plan_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",
+    "iso_validate_cfg", "iso_plan_chunks", "iso_plan_split", "iso_stack_prefill_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",
     "iso_layer_prefill", "iso_stack_prefill", "iso_attn_chunk", "iso_gemm_rowpar", "iso_rmsnorm",
     "iso_residual_rmsnorm", "iso_rope_kv_write", "iso_swiglu", "iso_set_flags", "iso_host_sink",
     "iso_timing_enable", "iso_timing_read",
@@ -87,6 +88,7 @@ def load() -> ctypes.CDLL:
     lib.iso_last_error.argtypes = []
     lib.iso_validate_cfg.argtypes = [ctypes.POINTER(IsoCfg)]
     lib.iso_plan_chunks.argtypes = [ctypes.POINTER(IsoCfg), ci, ci, ctypes.POINTER(IsoPlan)]
+    lib.iso_plan_split.argtypes = [ctypes.POINTER(IsoCfg), ci, ci, ctypes.c_double, ctypes.POINTER(ci)]
     lib.iso_create.argtypes = [pvp, ctypes.POINTER(IsoCfg), vp, vp]
     lib.iso_destroy.argtypes = [vp]
     lib.iso_sync.argtypes = [vp]
@@ -95,6 +97,8 @@ def load() -> ctypes.CDLL:
     lib.iso_host_sink.restype = vp
     lib.iso_layer_prefill.argtypes = [vp, ctypes.POINTER(IsoWeights), vp, vp, vp, ci, ci, ci, ci]
     lib.iso_stack_prefill.argtypes = [vp, ctypes.POINTER(IsoWeights), ci, vp, vp, vp, ci, ci, ci, ci]
+    lib.iso_stack_prefill_chunks.argtypes = [vp, ctypes.POINTER(IsoWeights), ci, vp, vp, vp, ci, ctypes.POINTER(ci), ci,
+                                             ci, ci]
     lib.iso_attn_chunk.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp]
     lib.iso_gemm_rowpar.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp, vp]
     lib.iso_rmsnorm.argtypes = [vp, vp, vp, vp, ci, vp]
@@ -156,6 +160,13 @@ def plan_chunks(cfg: IsoCfg, T: int, split: int) -> IsoPlan:
     plan = IsoPlan()
     _check(load().iso_plan_chunks(ctypes.byref(cfg), T, split, ctypes.byref(plan)))
     return plan
+
+
+def plan_split(cfg: IsoCfg, T: int, n_chunks: int, attn_flop_cost: float = 0.0) -> List[int]:
+    """Cut points for n_chunks chunks of equal estimated cost (attn_flop_cost <= 0: the library's default)."""
+    out = (ctypes.c_int * max(1, n_chunks - 1))()
+    _check(load().iso_plan_split(ctypes.byref(cfg), T, n_chunks, float(attn_flop_cost), out if n_chunks > 1 else None))
+    return [int(out[i]) for i in range(n_chunks - 1)]
 
 
 # ------------------------------------------------------------------------------ buffers and streams
@@ -366,6 +377,15 @@ class Context:
         arr = (IsoWeights * len(layers))(*[pack_weights(w) for w in layers])
         _check(self._lib.iso_stack_prefill(self._h, arr, len(layers), _ptr(x), _ptr(k_caches), _ptr(v_caches),
                                            T, split, comm, sched))
+
+    def stack_prefill_chunks(self, layers: Sequence[Dict[str, object]], x, k_caches, v_caches, T: int,
+                             bounds: Sequence[int], comm: int = ISO_COMM_NONE,
+                             sched: int = ISO_SCHED_OVERLAP) -> None:
+        """bounds: the ascending cut points; len(bounds) + 1 chunks."""
+        arr = (IsoWeights * len(layers))(*[pack_weights(w) for w in layers])
+        cuts = (ctypes.c_int * max(1, len(bounds)))(*[int(b) for b in bounds])
+        _check(self._lib.iso_stack_prefill_chunks(self._h, arr, len(layers), _ptr(x), _ptr(k_caches), _ptr(v_caches),
+                                                  T, cuts if len(bounds) else None, len(bounds) + 1, comm, sched))
 
     def attn_chunk(self, q, k_cache, v_cache, out, Tc: int, q_offset: int, kv_len: int, stream=None) -> None:
         _check(self._lib.iso_attn_chunk(self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), Tc, q_offset,

@@ -197,7 +197,8 @@ int attn_block_head(iso_ctx *ctx, const iso_weights *w, void *x, void *kc, void 
     return ISO_OK;
 }
 
-int attn_block_tail(iso_ctx *ctx, const iso_weights *w, void *kc, void *vc, const Chunk &ck, int comm) {
+int attn_block_tail(iso_ctx *ctx, const iso_weights *w, void *kc, void *vc, const Chunk &ck, int comm,
+                    hipEvent_t after_compute) {
     const iso_cfg &c = ctx->cfg;
     const size_t e = ctx->elt;
     const int H = c.hidden, NQKV = n_qkv(c), NQD = c.n_q_heads * c.head_dim;
@@ -206,7 +207,7 @@ int attn_block_tail(iso_ctx *ctx, const iso_weights *w, void *kc, void *vc, cons
     char *partr = at(ctx->part, ck.lo, H, e);
     ISO_TRY(attention(ctx, qkvr, NQKV, kc, vc, attnr, ck.n, ck.lo, ck.lo + ck.n, ck.s));
     ISO_TRY(gemm(ctx, ISO_K_GEMM_O, attnr, w->w_o, partr, ck.n, H, NQD, ck.s));
-    (void)partr;
+    if (after_compute) HIP_TRY(hipEventRecord(after_compute, ck.s));
     return comm_point(ctx, comm, 0, ck.lo, ck.n, ck.s);
 }
 
@@ -262,19 +263,36 @@ int check_layer_args(iso_ctx *ctx, const iso_weights *layers, int n_layers, void
     if (split < 0 || split > T) return fail(ISO_ERR_SPLIT, "split=%d outside [0, %d]", split, T);
     if (comm != ISO_COMM_NONE && comm != ISO_COMM_D2H && comm != ISO_COMM_D2H_INT8)
         return fail(ISO_ERR_SHAPE, "unknown comm mode %d", comm);
-    if (sched != ISO_SCHED_OVERLAP && sched != ISO_SCHED_SERIAL) return fail(ISO_ERR_SHAPE, "unknown schedule %d", sched);
+    if (sched != ISO_SCHED_OVERLAP && sched != ISO_SCHED_SERIAL && sched != ISO_SCHED_STREAM_PER_CHUNK)
+        return fail(ISO_ERR_SHAPE, "unknown schedule %d", sched);
     return ISO_OK;
 }
 
-int run_stack(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, void *k_caches, void *v_caches, int T,
-              int split, int comm, int sched) {
+// Extra streams for ISO_SCHED_STREAM_PER_CHUNK, created on first use (default priority, like every stream here).
+int chunk_streams(iso_ctx *ctx, int nc, hipStream_t *out) {
+    out[0] = ctx->stream[0];
+    out[1] = ctx->stream[1];
+    for (int k = 2; k < nc; ++k) {
+        if (!ctx->xstream[k]) HIP_TRY(hipStreamCreateWithFlags(&ctx->xstream[k], hipStreamNonBlocking));
+        out[k] = ctx->xstream[k];
+    }
+    return ISO_OK;
+}
+
+// edges[0..nc]: chunk c is rows [edges[c], edges[c+1]).
+int run_stack(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, void *k_caches, void *v_caches,
+              const int *edges, int nc, int comm, int sched) {
     const iso_cfg &c = ctx->cfg;
     const size_t cache_bytes = (size_t)c.max_seq * c.n_kv_heads * c.head_dim * ctx->elt;
-    const bool two = split > 0 && split < T;
-    const bool overlap = two && sched == ISO_SCHED_OVERLAP && ctx->stream[1] != ctx->stream[0];
-    hipStream_t s0 = ctx->stream[0], s1 = overlap ? ctx->stream[1] : ctx->stream[0];
-    Chunk ch[2] = {{0, two ? split : T, s0}, {split, T - split, s1}};
-    const int nc = two ? 2 : 1;
+    const bool overlap = nc > 1 && sched != ISO_SCHED_SERIAL && ctx->stream[1] != ctx->stream[0];
+    const bool per_chunk = overlap && sched == ISO_SCHED_STREAM_PER_CHUNK;
+    hipStream_t st[ISO_MAX_CHUNKS];
+    for (int k = 0; k < ISO_MAX_CHUNKS; ++k) st[k] = ctx->stream[0];
+    if (per_chunk) ISO_TRY(chunk_streams(ctx, nc, st));
+    else if (overlap) for (int k = 0; k < nc; ++k) st[k] = ctx->stream[k & 1];
+    const int n_streams = per_chunk ? nc : (overlap ? 2 : 1);
+    Chunk ch[ISO_MAX_CHUNKS];
+    for (int k = 0; k < nc; ++k) ch[k] = Chunk{edges[k], edges[k + 1] - edges[k], st[k]};
 
     // Stream-K takes every compute unit for one GEMM.  That pays while the other chunk's stream mostly waits for
     // its bf16 transfers; when two chunks compute side by side most of the time (no transfers, or the halved int8
@@ -284,31 +302,46 @@ int run_stack(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, vo
         ~SkHold() { c->sk_hold = 0; }
     } sk_hold_{ctx};
     ctx->sk_hold = overlap && comm != ISO_COMM_D2H;
-    if (overlap) {   // fork: stream1 starts after whatever produced x in stream0
-        HIP_TRY(hipEventRecord(ctx->ev_fork, s0));
-        HIP_TRY(hipStreamWaitEvent(s1, ctx->ev_fork, 0));
+    if (overlap) {   // fork: the other streams start after whatever produced x in stream0
+        HIP_TRY(hipEventRecord(ctx->ev_fork, st[0]));
+        for (int k = 1; k < n_streams; ++k) HIP_TRY(hipStreamWaitEvent(st[k], ctx->ev_fork, 0));
     }
     for (int l = 0; l < n_layers; ++l) {
         const iso_weights *w = &layers[l];
         void *kc = (char *)k_caches + (size_t)l * cache_bytes;
         void *vc = (char *)v_caches + (size_t)l * cache_bytes;
-        // A0 head, then the KV event, then A1 head: chunk 1's norm/QKV/RoPE do not depend on chunk 0.
+        // Heads first: the norm/QKV/RoPE of a chunk do not depend on any other chunk.  A chunk's attention then
+        // waits for an event of its predecessor, and through it for every earlier chunk:
+        //  * two streams: the event says the predecessor's K/V rows are in the cache; the predecessor sits on
+        //    the other stream, behind ITS predecessor's head on this one;
+        //  * one stream per chunk: the event follows the predecessor's output projection, so the attention blocks
+        //    run one after the other in chunk order and the first transfer starts as early as it can, instead of
+        //    all chunks sharing the chip and finishing together.
         for (int k = 0; k < nc; ++k) {
             ISO_TRY(attn_block_head(ctx, w, x, kc, vc, ch[k], l > 0));
-            if (k == 0 && overlap) HIP_TRY(hipEventRecord(ctx->ev_kv0, s0));
+            if (overlap && !per_chunk && k + 1 < nc) HIP_TRY(hipEventRecord(ctx->ev_kv[k], ch[k].s));
         }
         for (int k = 0; k < nc; ++k) {
-            if (k == 1 && overlap) HIP_TRY(hipStreamWaitEvent(s1, ctx->ev_kv0, 0));
-            ISO_TRY(attn_block_tail(ctx, w, kc, vc, ch[k], comm));
+            if (overlap && k > 0) HIP_TRY(hipStreamWaitEvent(ch[k].s, ctx->ev_kv[k - 1], 0));
+            ISO_TRY(attn_block_tail(ctx, w, kc, vc, ch[k], comm, (per_chunk && k + 1 < nc) ? ctx->ev_kv[k] : nullptr));
         }
         for (int k = 0; k < nc; ++k) ISO_TRY(mlp_block(ctx, w, x, ch[k], comm));
     }
     for (int k = 0; k < nc; ++k) ISO_TRY(final_residual(ctx, x, ch[k]));
-    if (overlap) {   // join: later work in stream0 sees both chunks
-        HIP_TRY(hipEventRecord(ctx->ev_join, s1));
-        HIP_TRY(hipStreamWaitEvent(s0, ctx->ev_join, 0));
+    if (overlap) {   // join: later work in stream0 sees every chunk
+        for (int k = 1; k < n_streams; ++k) {
+            HIP_TRY(hipEventRecord(ctx->ev_join[k], st[k]));
+            HIP_TRY(hipStreamWaitEvent(st[0], ctx->ev_join[k], 0));
+        }
     }
     return ISO_OK;
+}
+
+int run_split(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, void *k_caches, void *v_caches, int T,
+              int split, int comm, int sched) {
+    const bool two = split > 0 && split < T;
+    const int edges[3] = {0, two ? split : T, T};
+    return run_stack(ctx, layers, n_layers, x, k_caches, v_caches, edges, two ? 2 : 1, comm, sched);
 }
 
 }  // namespace
@@ -339,6 +372,36 @@ int iso_plan_chunks(const iso_cfg *cfg, int T, int split, iso_plan *out) {
     for (int k = 0; k < out->n_chunks; ++k)
         out->comm_bytes[k] = (size_t)out->n_tokens[k] * cfg->hidden * elt_size(cfg->dtype);
     out->workspace_bytes = ws_layout(*cfg).total;
+    return ISO_OK;
+}
+
+int iso_plan_split(const iso_cfg *cfg, int T, int n_chunks, double attn_flop_cost, int *bounds) {
+    ISO_TRY(check_cfg(cfg));
+    if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
+    if (T > cfg->max_seq) return fail(ISO_ERR_WORKSPACE, "T=%d exceeds max_seq=%d", T, cfg->max_seq);
+    if (n_chunks < 1 || n_chunks > ISO_MAX_CHUNKS || n_chunks > T)
+        return fail(ISO_ERR_SHAPE, "n_chunks=%d outside [1, min(T, %d)]", n_chunks, ISO_MAX_CHUNKS);
+    if (n_chunks > 1 && !bounds) return fail(ISO_ERR_NULL, "bounds is NULL");
+    const double r = attn_flop_cost > 0.0 ? attn_flop_cost : 3.0;
+    const double nq = cfg->n_q_heads, nkv = cfg->n_kv_heads, d = cfg->head_dim, H = cfg->hidden, F = cfg->ffn;
+    // cumulative cost of the first t positions: proj * t + a * t * (t + 1), a = r * 2 * nq * d
+    const double proj = 2.0 * H * (nq + 2.0 * nkv) * d + 2.0 * H * nq * d + 6.0 * H * F;
+    const double a = r * 2.0 * nq * d;
+    const double total = proj * T + a * (double)T * (T + 1.0);
+    const int align = T >= 256 * n_chunks ? 128 : 1;
+    int prev = 0;
+    for (int j = 1; j < n_chunks; ++j) {
+        const double target = total * j / n_chunks;
+        const double b = proj + a;
+        const double t = (sqrt(b * b + 4.0 * a * target) - b) / (2.0 * a);    // a > 0 for every valid cfg
+        long cut = lround(t / align) * align;
+        if (cut <= prev) cut = prev + align;              // at least one (aligned) step per chunk ...
+        const long last = (long)T - (long)(n_chunks - j);
+        if (cut > last) cut = last;                       // ... and room for the chunks behind
+        if (cut <= prev) cut = prev + 1;
+        bounds[j - 1] = (int)cut;
+        prev = (int)cut;
+    }
     return ISO_OK;
 }
 
@@ -410,8 +473,13 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
             if (!ok) break;
         }
         if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming), "event")) break;
-        if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming), "event")) break;
-        if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_kv0, hipEventDisableTiming), "event")) break;
+        {
+            bool ok = true;
+            for (int k = 0; k < ISO_MAX_CHUNKS && ok; ++k)
+                ok = hip_ok(hipEventCreateWithFlags(&ctx->ev_join[k], hipEventDisableTiming), "event") &&
+                     hip_ok(hipEventCreateWithFlags(&ctx->ev_kv[k], hipEventDisableTiming), "event");
+            if (!ok) break;
+        }
     } while (0);
     if (rc != ISO_OK) {
         char keep[sizeof(g_err)];
@@ -449,8 +517,11 @@ int iso_destroy(iso_ctx *ctx) {
     delete[] ctx->tev1;
     delete[] ctx->tkind;
     if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
-    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
-    if (ctx->ev_kv0) (void)hipEventDestroy(ctx->ev_kv0);
+    for (int k = 0; k < ISO_MAX_CHUNKS; ++k) {
+        if (ctx->ev_join[k]) (void)hipEventDestroy(ctx->ev_join[k]);
+        if (ctx->ev_kv[k]) (void)hipEventDestroy(ctx->ev_kv[k]);
+        if (ctx->xstream[k]) (void)hipStreamDestroy(ctx->xstream[k]);
+    }
     if (ctx->sk[0].err) (void)hipHostFree(ctx->sk[0].err);
     for (int i = 0; i < 2; ++i)
         if (ctx->sk[i].base) (void)hipFree(ctx->sk[i].base);
@@ -554,13 +625,30 @@ void *iso_host_sink(iso_ctx *ctx) { return ctx ? ctx->host_sink : nullptr; }
 int iso_layer_prefill(iso_ctx *ctx, const iso_weights *w, void *x, void *k_cache, void *v_cache, int T, int split,
                       int comm, int sched) {
     ISO_TRY(check_layer_args(ctx, w, 1, x, k_cache, v_cache, T, split, comm, sched));
-    return run_stack(ctx, w, 1, x, k_cache, v_cache, T, split, comm, sched);
+    return run_split(ctx, w, 1, x, k_cache, v_cache, T, split, comm, sched);
 }
 
 int iso_stack_prefill(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, void *k_caches, void *v_caches,
                       int T, int split, int comm, int sched) {
     ISO_TRY(check_layer_args(ctx, layers, n_layers, x, k_caches, v_caches, T, split, comm, sched));
-    return run_stack(ctx, layers, n_layers, x, k_caches, v_caches, T, split, comm, sched);
+    return run_split(ctx, layers, n_layers, x, k_caches, v_caches, T, split, comm, sched);
+}
+
+int iso_stack_prefill_chunks(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, void *k_caches,
+                             void *v_caches, int T, const int *bounds, int n_chunks, int comm, int sched) {
+    ISO_TRY(check_layer_args(ctx, layers, n_layers, x, k_caches, v_caches, T, 0, comm, sched));
+    if (n_chunks < 1 || n_chunks > ISO_MAX_CHUNKS)
+        return fail(ISO_ERR_SHAPE, "n_chunks=%d outside [1, %d]", n_chunks, ISO_MAX_CHUNKS);
+    if (n_chunks > 1 && !bounds) return fail(ISO_ERR_NULL, "bounds is NULL");
+    int edges[ISO_MAX_CHUNKS + 1];
+    edges[0] = 0;
+    for (int k = 1; k < n_chunks; ++k) {
+        edges[k] = bounds[k - 1];
+        if (edges[k] <= edges[k - 1] || edges[k] >= T)
+            return fail(ISO_ERR_SPLIT, "bounds[%d]=%d must lie in (%d, %d)", k - 1, edges[k], edges[k - 1], T);
+    }
+    edges[n_chunks] = T;
+    return run_stack(ctx, layers, n_layers, x, k_caches, v_caches, edges, n_chunks, comm, sched);
 }
 
 int iso_attn_chunk(iso_ctx *ctx, const void *q, const void *k_cache, const void *v_cache, void *out, int Tc,

@@ -28,7 +28,8 @@ struct iso_ctx {
     int device;
     int flags;
     hipStream_t stream[2];
-    hipEvent_t ev_fork, ev_join, ev_kv0;
+    hipStream_t xstream[ISO_MAX_CHUNKS];   // own streams for chunks 2.. of ISO_SCHED_STREAM_PER_CHUNK, made on first use
+    hipEvent_t ev_fork, ev_join[ISO_MAX_CHUNKS], ev_kv[ISO_MAX_CHUNKS];
     size_t elt;        // bytes per element
     // device workspace, each sized for max_seq tokens; chunks use disjoint row ranges
     void *ws;          // one allocation
@@ -44,7 +45,7 @@ struct iso_ctx {
     float *rope_cos;   // [max_seq, d/2]
     float *rope_sin;   // [max_seq, d/2]
     int sk_hold;       // set while a pass enqueues work for which stream-K is not to be picked
-    iso_sk_ws sk[2];   // stream-K GEMM workspaces, one per stream (bf16 contexts only; base == null otherwise)
+    iso_sk_ws sk[2];   // stream-K GEMM workspaces, one per caller stream (bf16 contexts only; base == null otherwise)
     void *host_sink;   // pinned, 2 * max_seq * hidden elements
     // optional per-launch timing (iso_timing_*): event pairs recorded around every launch, in its stream
     int timing;

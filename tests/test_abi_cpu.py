@@ -65,6 +65,32 @@ def test_plan_chunks():
         assert ei.value.code == code
 
 
+def test_plan_split_balances_cost_like_the_oracles_definition():
+    """The library's closed-form cut points against the oracle's cumulative-cost definition (Section 6): equal
+    up to the rounding to multiples of 128 (of 1 for short prompts)."""
+    import numpy as np
+    from oracle import iso_oracle as orc
+    for (hidden, nq, nkv, d, ffn) in ((6656, 13, 13, 128, 4480), (8192, 8, 1, 128, 3584), (256, 4, 4, 64, 688)):
+        cfg = _good_cfg(max_seq=131072, hidden=hidden, dtype=iso.ISO_BF16, head_dim=d, n_q_heads=nq, n_kv_heads=nkv,
+                        ffn=ffn)
+        sh = orc.LayerShape(hidden, nq, nkv, d, ffn, 1e-6, 1e4)
+        for T, n, r in ((2048, 2, 3.0), (8192, 4, 3.0), (16384, 8, 1.0), (131072, 4, 5.0), (300, 4, 3.0), (37, 8, 2.0)):
+            got = iso.plan_split(cfg, T, n, r)
+            want = orc.balanced_cuts(sh, T, n, r)
+            align = 128 if T >= 256 * n else 1
+            assert len(got) == n - 1 and all(b > a for a, b in zip([0] + got, got + [T]))
+            assert all(g % align == 0 for g in got)
+            assert np.all(np.abs(np.array(got) - want) <= align / 2 + 1), (T, n, got, want)
+        assert iso.plan_split(cfg, 4096, 4, 0.0) == iso.plan_split(cfg, 4096, 4, 3.0)      # the default ratio
+        assert iso.plan_split(cfg, 4096, 1) == []
+        assert iso.plan_split(cfg, 5, 5) == [1, 2, 3, 4]
+    for T, n, code in ((0, 2, iso.ISO_ERR_SHAPE), (100, 0, iso.ISO_ERR_SHAPE), (100, 9, iso.ISO_ERR_SHAPE),
+                       (3, 4, iso.ISO_ERR_SHAPE), (131073, 2, iso.ISO_ERR_WORKSPACE)):
+        with pytest.raises(iso.IsoError) as ei:
+            iso.plan_split(cfg, T, n)
+        assert ei.value.code == code
+
+
 def test_null_context_and_null_out_are_refused_without_touching_a_device():
     lib = iso.load()
     w = iso.IsoWeights()

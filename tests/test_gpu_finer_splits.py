@@ -1,0 +1,126 @@
+"""GPU parity of the finer-grained schedules (Section 6): more than two chunks, cost-balanced cut points, one
+stream per chunk.  Same tolerances and metric as test_gpu_parity.py."""
+import numpy as np
+import pytest
+
+import paper_2409_11155_amd as iso      # first: binds libiso to the HIP runtime it was built against
+import iso_inputs
+from oracle import iso_oracle as orc
+from test_gpu_parity import (NAN_BYTE, TOL_LAYER, TOL_STEP, dev, f64, h64, make_ctx, oracle_weights, shape_of)
+
+pytestmark = pytest.mark.gpu
+
+SCHEDS = (iso.ISO_SCHED_OVERLAP, iso.ISO_SCHED_SERIAL, iso.ISO_SCHED_STREAM_PER_CHUNK)
+
+
+def run_chunks(ctx, layers_dev, x_host, dt, T, bounds, nkv, d, max_seq, comm, sched):
+    x = dev(x_host, dt)
+    L = len(layers_dev)
+    kc = iso.DeviceArray((L, max_seq, nkv, d), dt, fill_byte=NAN_BYTE)
+    vc = iso.DeviceArray((L, max_seq, nkv, d), dt, fill_byte=NAN_BYTE)
+    ctx.stack_prefill_chunks(layers_dev, x, kc, vc, T, bounds, comm, sched)
+    ctx.sync()
+    return x, kc, vc
+
+
+def test_tiny_f32_layer_in_three_to_eight_chunks():
+    wl = iso_inputs.WORKLOADS["tiny_f32"]
+    x, w = iso_inputs.make_workload_inputs(wl, seed=0)
+    sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
+    ref = orc.layer_unsplit(h64(x, "f32"), oracle_weights(w, "f32"), sh)
+    w_dev = [iso.upload_weights(w, "f32")]
+    cases = [[], [64], [40, 90], [1, 2, 127], [16, 32, 64, 100], [10, 20, 30, 40, 50, 60, 70]]
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, "f32", wl.seq) as ctx:
+        for bounds in cases:
+            # the oracle's chunked path with the same cuts agrees with its unsplit path (pinned on the CPU) ...
+            if bounds:
+                ref_iso = orc.layer_iso(h64(x, "f32"), oracle_weights(w, "f32"), sh, bounds)
+                assert orc.max_rel_err(ref_iso["x_out"], ref["x_out"]) <= 1e-12
+            for sched in SCHEDS:
+                for comm in (iso.ISO_COMM_NONE, iso.ISO_COMM_D2H):
+                    out, kc, vc = run_chunks(ctx, w_dev, x, "f32", wl.seq, bounds, wl.n_kv_heads, wl.head_dim, wl.seq,
+                                             comm, sched)
+                    err = orc.max_rel_err(f64(out), ref["x_out"])
+                    assert err <= TOL_LAYER["f32"], (bounds, sched, comm, err)   # ... and so does the device
+                    assert orc.max_rel_err(f64(kc)[0], ref["k_cache"]) <= TOL_STEP["f32"]
+                    assert orc.max_rel_err(f64(vc)[0], ref["v_cache"]) <= TOL_STEP["f32"]
+
+
+@pytest.mark.parametrize("sched", SCHEDS)
+def test_small_bf16_two_layer_stack_in_four_chunks(sched):
+    hidden, nq, nkv, d, ffn, T, dt = 512, 4, 1, 128, 768, 300, "bf16"
+    layers = [iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=40 + l, dtype=dt) for l in range(2)]
+    x = iso_inputs.make_hidden(T, hidden, seed=6, dtype=dt)
+    sh = shape_of(hidden, nq, nkv, d, ffn)
+    ref = h64(x, dt)
+    refs = []
+    for w in layers:
+        r = orc.layer_unsplit(ref, oracle_weights(w, dt), sh)
+        refs.append(r)
+        ref = r["x_out"]
+    layers_dev = [iso.upload_weights(w, dt) for w in layers]
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, 320) as ctx:
+        for bounds in ([70, 150, 299], [128, 129, 130]):
+            out, kc, vc = run_chunks(ctx, layers_dev, x, dt, T, bounds, nkv, d, 320, iso.ISO_COMM_D2H, sched)
+            # two layers compound the per-layer bf16 error: allow twice the per-layer bound
+            assert orc.max_rel_err(f64(out), ref) <= 2 * TOL_LAYER[dt], bounds
+            assert orc.max_rel_err(f64(kc)[0, :T], refs[0]["k_cache"]) <= TOL_LAYER[dt]
+            assert orc.max_rel_err(f64(vc)[0, :T], refs[0]["v_cache"]) <= TOL_LAYER[dt]
+
+
+def test_schedules_agree_bit_for_bit_and_never_read_an_unwritten_cache_row():
+    """The three schedules enqueue the same kernels on the same rows, so their outputs are identical bits; the
+    cache starts as NaN, so an attention block that overtook an earlier chunk's K/V write would show as NaN."""
+    hidden, nq, nkv, d, ffn, T, dt = 1024, 8, 1, 128, 1024, 1024, "bf16"
+    w = [iso.upload_weights(iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=3, dtype=dt), dt)]
+    x = iso_inputs.make_hidden(T, hidden, seed=3, dtype=dt)
+    bounds = [256, 512, 768]
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, T) as ctx:
+        ctx.set_flags(iso.ISO_FLAG_NO_STREAMK)     # stream-K changes the fp32 sum order, not the point here
+        first = None
+        for rep in range(4):
+            for sched in SCHEDS:
+                out, _, _ = run_chunks(ctx, w, x, dt, T, bounds, nkv, d, T, iso.ISO_COMM_D2H, sched)
+                bits = out.numpy()
+                assert not np.isnan(iso_inputs.bf16_bits_to_f32(bits)).any()
+                if first is None:
+                    first = bits
+                np.testing.assert_array_equal(bits, first)
+
+
+@pytest.mark.parametrize("n_chunks,sched", [(4, iso.ISO_SCHED_OVERLAP), (4, iso.ISO_SCHED_STREAM_PER_CHUNK),
+                                            (3, iso.ISO_SCHED_STREAM_PER_CHUNK)])
+def test_full_size_30b_tp4_2k_cost_balanced_chunks_sampled_rows(n_chunks, sched):
+    wl = iso_inputs.WORKLOADS["30b_tp4_2k"]
+    dt = wl.dtype
+    x, w = iso_inputs.make_workload_inputs(wl, seed=0)
+    cfg = iso.make_cfg(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, wl.seq)
+    bounds = iso.plan_split(cfg, wl.seq, n_chunks)
+    rows = np.unique(np.concatenate([iso_inputs.sample_rows(wl.seq, b, 24, seed=b) for b in bounds]))
+    sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
+    ref = orc.layer_rows(h64(x, dt), oracle_weights(w, dt), sh, rows)
+    with iso.Context(cfg) as ctx:
+        out, kc, vc = run_chunks(ctx, [iso.upload_weights(w, dt)], x, dt, wl.seq, bounds, wl.n_kv_heads, wl.head_dim,
+                                 wl.seq, iso.ISO_COMM_D2H, sched)
+        err = orc.max_rel_err(f64(out)[rows], ref["x_out"])
+        assert err <= TOL_LAYER[dt], (bounds, err)
+        assert orc.max_rel_err(f64(kc)[0], ref["k_cache"]) <= TOL_LAYER[dt]
+        assert orc.max_rel_err(f64(vc)[0], ref["v_cache"]) <= TOL_LAYER[dt]
+
+
+def test_chunked_prefill_rejects_bad_arguments():
+    wl = iso_inputs.WORKLOADS["tiny_f32"]
+    x, w = iso_inputs.make_workload_inputs(wl, seed=0)
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, "f32", wl.seq) as ctx:
+        w_dev = [iso.upload_weights(w, "f32")]
+        xd = dev(x, "f32")
+        kc = iso.DeviceArray((wl.seq, wl.n_kv_heads, wl.head_dim), "f32", fill_byte=0)
+        vc = iso.DeviceArray((wl.seq, wl.n_kv_heads, wl.head_dim), "f32", fill_byte=0)
+        for bounds, code in (([64, 64], iso.ISO_ERR_SPLIT), ([90, 40], iso.ISO_ERR_SPLIT), ([0], iso.ISO_ERR_SPLIT),
+                             ([wl.seq], iso.ISO_ERR_SPLIT), (list(range(1, 9)), iso.ISO_ERR_SHAPE)):
+            with pytest.raises(iso.IsoError) as ei:
+                ctx.stack_prefill_chunks(w_dev, xd, kc, vc, wl.seq, bounds)
+            assert ei.value.code == code, bounds
+        with pytest.raises(iso.IsoError) as ei:
+            ctx.stack_prefill_chunks(w_dev, xd, kc, vc, wl.seq, [64], sched=7)
+        assert ei.value.code == iso.ISO_ERR_SHAPE

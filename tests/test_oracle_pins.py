@@ -321,6 +321,48 @@ def test_split_invariance_for_every_split_point():
         assert orc.max_rel_err(got["v_cache"], ref["v_cache"]) < 1e-13, s
 
 
+def test_split_invariance_for_finer_cuts():
+    """Section 6: any finer segmentation of the prompt is still the same layer.  Random partitions into
+    3..8 chunks, including one-token chunks, against the unsplit prefill."""
+    wl, x, w, sh = _tiny()
+    ref = orc.layer_unsplit(x, w, sh)
+    gen = np.random.default_rng(5)
+    cases = [[1, 2], [wl.seq - 2, wl.seq - 1], list(range(16, wl.seq, 16))]
+    for n in range(3, 9):
+        cases.append(sorted(int(c) for c in gen.choice(np.arange(1, wl.seq), size=n - 1, replace=False)))
+    for cuts in cases:
+        got = orc.layer_iso(x, w, sh, cuts)
+        assert orc.max_rel_err(got["x_out"], ref["x_out"]) < 1e-12, cuts
+        assert orc.max_rel_err(got["k_cache"], ref["k_cache"]) < 1e-13, cuts
+    for bad in ([0], [wl.seq], [40, 40], [50, 30]):
+        with pytest.raises(ValueError):
+            orc.layer_iso(x, w, sh, bad)
+
+
+def test_token_cost_and_balanced_cuts():
+    """Section 6: cut by cost, not by length.  Pins: the hand-computed cost of one position; without an
+    attention term the cuts are equal lengths; with it every chunk costs the same to within one token and
+    the first chunk is the longest; the two-chunk cut solves the quadratic of the continuous cost."""
+    sh = orc.LayerShape(hidden=8, n_q_heads=2, n_kv_heads=1, head_dim=4, ffn=16, rms_eps=1e-6, rope_base=1e4)
+    # projections: qkv 2*8*(2+2)*4 = 256, o 2*8*8 = 128, gate/up/down 6*8*16 = 768 -> 1152; attention at
+    # position 2 (3 keys): 4 * 2 * 4 * 3 = 96 flops, weighted by 2.5
+    assert orc.token_cost(sh, 5, 2.5)[2] == 1152 + 2.5 * 96
+    np.testing.assert_allclose(orc.balanced_cuts(sh, 120, 4, 0.0), [30, 60, 90], rtol=0, atol=1e-9)
+    big = orc.LayerShape(hidden=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2048, rms_eps=1e-6, rope_base=1e4)
+    T, n = 4096, 4
+    cost = orc.token_cost(big, T, 3.0)
+    cuts = orc.balanced_cuts(big, T, n, 3.0)
+    edges = np.concatenate([[0], np.round(cuts).astype(int), [T]])
+    per_chunk = np.array([cost[a:b].sum() for a, b in zip(edges[:-1], edges[1:])])
+    assert np.all(np.abs(per_chunk - cost.sum() / n) <= cost.max())
+    lengths = np.diff(edges)
+    assert np.all(np.diff(lengths) < 0)          # strictly shorter chunks towards the dear end
+    # two chunks: proj * t + a * t * (t + 1) = total / 2 with a = 3 * 2 * nq * d
+    proj, a = cost[0] - 3.0 * 4 * 8 * 128, 3.0 * 2 * 8 * 128
+    t = orc.balanced_cuts(big, T, 2, 3.0)[0]
+    assert abs(proj * t + a * t * (t + 1) - cost.sum() / 2) <= cost.max()
+
+
 def test_causality_later_tokens_do_not_touch_earlier_rows():
     wl, x, w, sh = _tiny()
     p = 40
