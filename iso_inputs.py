@@ -105,6 +105,11 @@ WORKLOADS: Dict[str, Workload] = {
         Workload("70b_tp4_8k", 8192, 16, 2, 128, 7168, 8192, 4096, "bf16"),
         # ~70B GQA model, one TP=8 shard, full 80-layer stack, 16k prompt
         Workload("70b_tp8_16k_stack", 8192, 8, 1, 128, 3584, 16384, 8192, "bf16", n_layers=80),
+        # the long prompts of the paper's Table 1 at the same shard: attention grows from a quarter to most of the
+        # flops; the cut leaves the first chunk the longer one (Section 6)
+        Workload("70b_tp8_32k", 8192, 8, 1, 128, 3584, 32768, 18432, "bf16"),
+        Workload("70b_tp8_64k", 8192, 8, 1, 128, 3584, 65536, 37888, "bf16"),
+        Workload("70b_tp8_128k", 8192, 8, 1, 128, 3584, 131072, 77824, "bf16"),
     ]
 }
 

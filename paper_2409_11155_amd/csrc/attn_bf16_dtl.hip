@@ -31,7 +31,7 @@ typedef __bf16 bf16x4_v __attribute__((ext_vector_type(4)));
 // workgroups share a compute unit and hide each other's latency; four stages (128 KB) are for launches too
 // small to fill the chip twice over, where the only thing hiding the load latency is the prefetch distance.
 template <int NSTAGE>
-__global__ __launch_bounds__(256) void attn_bf16_dtl_kernel(const bf16_t *__restrict__ Q,
+__global__ __launch_bounds__(256, 2) void attn_bf16_dtl_kernel(const bf16_t *__restrict__ Q,
                                                             const bf16_t *__restrict__ Kc,
                                                             const bf16_t *__restrict__ Vc,
                                                             bf16_t *__restrict__ Out, int Tc, int q_offset,
@@ -141,40 +141,48 @@ __global__ __launch_bounds__(256) void attn_bf16_dtl_kernel(const bf16_t *__rest
                 s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[sub], 0, 0, 0);
             }
         }
-        // --- mask (only tiles that touch the diagonal or the end of the cache), scale to log2 domain
+        // --- mask (only tiles that touch the diagonal or the end of the cache).  The scores stay unscaled: the
+        //     softmax scale is positive, so the running maximum can be kept in raw units and the scale folded
+        //     into the exponent's multiply-add.
         const bool need_mask = (j0 + BN - 1 > q_offset + m0 + wave * 32) || (j0 + BN > kv_len);
         float mx = -INFINITY;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float v = s[sub][r] * sc;
+                float v = s[sub][r];
                 if (need_mask) {
                     const int key = j0 + sub * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4);
                     if (key > q_abs || key >= kv_len) v = -INFINITY;
+                    s[sub][r] = v;
                 }
-                s[sub][r] = v;
                 mx = fmaxf(mx, v);
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        const float neg_m = -m_new * sc;
         float psum = 0.f;
         bf16x8_t pb[2][2];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(s[sub][r] - m_new);
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][r], sc, neg_m));
                 psum += p;
                 pb[sub][r / 8][r % 8] = (bf16_t)p;
             }
-        l_run = l_run * alpha + psum;
+        // rescale the running sums only when some row of this wave saw a new maximum (wave-uniform branch):
+        // deep into a long cache the maxima have settled and the 64 multiplies per tile are skipped
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+            m_run = m_new;
+            l_run *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
+            for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        }
+        l_run += psum;
         // --- O^T += V^T P^T.  k-slots 8*lgrp .. +8 of MFMA step (sub, t) hold keys
         //     32 sub + 16 t + 4 lgrp + {0..3} and 32 sub + 16 t + 8 + 4 lgrp + {0..3}: two transposing reads.
 #pragma unroll

@@ -392,6 +392,11 @@ def test_full_size_70b_tp4_8k_sampled_rows(split):
     _sampled_parity("70b_tp4_8k", split, n_rows=48)
 
 
+def test_full_size_70b_tp8_32k_long_prompt_sampled_rows():
+    """Long prompt of the paper's Table 1: attention over 32k keys is a quarter of the layer's flops."""
+    _sampled_parity("70b_tp8_32k", 18432, n_rows=32)
+
+
 def test_stack_at_70b_tp8_16k_shape_layer_by_layer():
     """Three layers of the 80-layer 70B TP=8 stack shape at the full 16k prompt, split 8192/8192, chunks kept on
     their streams across layers.  The bf16 bound is per layer, so each layer is checked from the GPU's own input
