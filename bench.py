@@ -133,6 +133,41 @@ def main() -> int:
                             "t_nocomm_ms": timed_chunks(bounds, NONE, sched)}
         finer[str(n_chunks)] = entry
 
+    # Section 3.2, computation-dominated case: (a) how much a kernel slows down while the copy engine runs beside it
+    # (the paper's collectives take compute units; these copies go through the DMA engines), (b) the layer with every
+    # projection cut into several launches.
+    def gate_up_alone_vs_beside_copies():
+        M, N, Kd = (split if 0 < split < T else T), 2 * wl.ffn, wl.hidden
+        a, wgu = x0, layers[0]["w_gate_up"]              # the workload's own (random) activations and weights
+        c = iso.DeviceArray((M, N), dt, fill_byte=0)
+        nbytes = min(128 << 20, M * N * iso.DTYPE_BYTES[dt])
+        out = {}
+        for label, copies in (("alone", 0), ("beside_copies", 24)):
+            for _ in range(3):
+                ctx.gemm_rowpar(a, wgu, c, M, N, Kd, ctx.stream0)
+            ctx.sync()
+            for _ in range(copies):
+                iso.copy_d2h_async(sink_buf, c, nbytes, ctx.stream1)
+            ctx.timing_enable(True)
+            for _ in range(10):
+                ctx.gemm_rowpar(a, wgu, c, M, N, Kd, ctx.stream0)
+            ms = ctx.timing_read()["gemm_o"][0] / 10
+            ctx.timing_enable(False)
+            ctx.sync()
+            out[label + "_ms"] = ms
+        out["slowdown"] = out["beside_copies_ms"] / out["alone_ms"] - 1.0
+        out["shape"] = {"M": M, "N": N, "K": Kd}
+        return out
+
+    sink_buf = iso.PinnedArray((64 << 20,), "bf16")      # 128 MiB of pinned memory for the copies of (a)
+    seg = {"gate_up_gemm": gate_up_alone_vs_beside_copies(), "t_iso_ms": {}, "t_iso_nocomm_ms": {}}
+    sink_buf.free()
+    for n_seg in (1, 2, 4):
+        ctx.set_gemm_segments(n_seg)
+        seg["t_iso_ms"][str(n_seg)] = timed(split, D2H, OVL)
+        seg["t_iso_nocomm_ms"][str(n_seg)] = timed(split, NONE, OVL)
+    ctx.set_gemm_segments(1)
+
     # ---- per-kernel durations, measured live with HIP events in the launch streams ----------------
     def kinds(sp, comm, sched, steps):
         x.copy_from(x0)
@@ -250,6 +285,9 @@ def main() -> int:
                          "sum_copy_ms": k_int8["comm"][0], "sum_quant_ms": k_int8["quant"][0],
                          "note": "partials quantised per token row to int8 before the copy (Section 3.2); "
                                  "not the headline: the headline moves the bf16 partial"},
+        "gemm_segmentation": dict(seg, note="Section 3.2: projections issued as 1, 2 or 4 launches along M; the copies "
+                                            "run on the DMA engines, so the contention this remedy addresses is "
+                                            "what gate_up_gemm.slowdown measures"),
         "finer_splits": {"chunks": finer,
                          "note": "Section 6: cost-balanced cuts into more than two chunks; not the headline, which is "
                                  "the two-chunk schedule at the workload's split"},

@@ -206,6 +206,12 @@ enum {
 };
 int iso_set_flags(iso_ctx *ctx, int flags);
 
+/* GEMM segmentation (Section 3.2, the remedy for the computation-dominated case): every projection of the layer
+ * entry points is issued as n launches over consecutive row ranges (multiples of 256 rows; products with fewer
+ * than 256 * n rows stay whole).  Results are unchanged bit for bit except where the stream-K kernel is picked
+ * for one size and not the other.  n in [1, 16]; 1 (the default) is one launch.  Errors: NULL, ISO_ERR_SHAPE. */
+int iso_set_gemm_segments(iso_ctx *ctx, int n);
+
 /* Per-launch timing for measurement.  While enabled, every kernel launch and every copy the library
  * enqueues is bracketed by a pair of HIP events recorded in the stream of that launch (at most 8192
  * launches are kept; enabling clears the record).  iso_timing_read synchronises both streams and returns
@@ -230,6 +236,9 @@ int iso_host_alloc(void **ptr, size_t bytes);             /* pinned host memory 
 int iso_host_free(void *ptr);
 int iso_copy_h2d(void *dst_dev, const void *src_host, size_t bytes);
 int iso_copy_d2h(void *dst_host, const void *src_dev, size_t bytes);
+/* Asynchronous device-to-host copy in `stream` (dst_host pinned, e.g. from iso_host_alloc): the same call the
+ * communication stand-in makes, exposed so that a caller can keep the copy engine busy beside a kernel. */
+int iso_copy_d2h_async(void *dst_host, const void *src_dev, size_t bytes, void *stream);
 int iso_copy_d2d(void *dst_dev, const void *src_dev, size_t bytes);
 int iso_stream_create(void **stream);                     /* non-blocking stream, default priority  */
 int iso_stream_destroy(void *stream);

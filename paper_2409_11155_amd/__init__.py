@@ -36,7 +36,7 @@ EXPORTS = [
     "iso_residual_rmsnorm", "iso_rope_kv_write", "iso_swiglu", "iso_set_flags", "iso_host_sink",
     "iso_timing_enable", "iso_timing_read",
     "iso_device_count", "iso_device_sync", "iso_dev_alloc", "iso_dev_free", "iso_dev_fill", "iso_host_alloc",
-    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
+    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2h_async", "iso_set_gemm_segments", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
 ]
 KERNEL_KINDS = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn", "rmsnorm", "resid_norm", "residual",
                 "rope_kv", "swiglu", "comm", "quant"]
@@ -116,6 +116,8 @@ def load() -> ctypes.CDLL:
     lib.iso_host_free.argtypes = [vp]
     lib.iso_copy_h2d.argtypes = [vp, vp, sz]
     lib.iso_copy_d2h.argtypes = [vp, vp, sz]
+    lib.iso_copy_d2h_async.argtypes = [vp, vp, sz, vp]
+    lib.iso_set_gemm_segments.argtypes = [vp, ci]
     lib.iso_copy_d2d.argtypes = [vp, vp, sz]
     lib.iso_stream_create.argtypes = [pvp]
     lib.iso_stream_destroy.argtypes = [vp]
@@ -292,6 +294,11 @@ def _ptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
+def copy_d2h_async(dst: "PinnedArray", src: "DeviceArray", nbytes: int, stream) -> None:
+    """Asynchronous device-to-host copy of the first nbytes of src into pinned memory, in `stream`."""
+    _check(load().iso_copy_d2h_async(dst.ptr, src.ptr, int(nbytes), _stream_handle(stream)))
+
+
 def _stream_handle(s) -> Optional[int]:
     if s is None:
         return None
@@ -347,6 +354,9 @@ class Context:
     # ---- entry points (same names as the C ABI, without the prefix) ----------------------------
     def sync(self) -> None:
         _check(self._lib.iso_sync(self._h))
+
+    def set_gemm_segments(self, n: int) -> None:
+        _check(self._lib.iso_set_gemm_segments(self._h, n))
 
     def set_flags(self, flags: int) -> None:
         _check(self._lib.iso_set_flags(self._h, flags))

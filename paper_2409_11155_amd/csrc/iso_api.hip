@@ -107,18 +107,38 @@ iso_sk_ws *sk_for(iso_ctx *ctx, hipStream_t s) {
     return nullptr;
 }
 
+// Row ranges of a GEMM cut into ctx->gemm_segments launches (Section 3.2: several launches per matrix product,
+// so that compute units given back by a finishing transfer are picked up at the next launch).  Segments are
+// multiples of 256 rows; a product with fewer than 256 rows per segment is not cut.
+template <typename F> int for_segments(const iso_ctx *ctx, int M, F &&launch) {
+    int segs = ctx->gemm_segments > 1 ? ctx->gemm_segments : 1;
+    if (M < 256 * segs) segs = 1;
+    const int per = ((M + segs - 1) / segs + 255) / 256 * 256;
+    for (int lo = 0; lo < M; lo += per) {
+        const int rc = launch(lo, M - lo < per ? M - lo : per);
+        if (rc != ISO_OK) return rc;
+    }
+    return ISO_OK;
+}
+
 int gemm(iso_ctx *ctx, int kind, const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     Timed t_(ctx, kind, s);
-    hipError_t e;
-    const bool mfma = ctx->cfg.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_GEMM);
-    if (mfma && !(ctx->flags & ISO_FLAG_GEMM_STAGED) && iso_gemm_bf16_dtl_supported(M, N, K))
-        e = iso_launch_gemm_bf16_dtl(a, w, c, M, N, K, (ctx->flags >> 8) & 15, sk_for(ctx, s), s);
-    else if (mfma && iso_gemm_bf16_mfma_supported(M, N, K))
-        e = iso_launch_gemm_bf16_mfma(a, w, c, M, N, K, s);
-    else
-        e = iso_launch_gemm_simple(ctx->cfg.dtype, a, w, c, M, N, K, s);
-    if (e != hipSuccess) return fail(ISO_ERR_HIP, "gemm launch (M=%d N=%d K=%d): %s", M, N, K, hipGetErrorString(e));
-    return ISO_OK;
+    const size_t e_ = ctx->elt;
+    return for_segments(ctx, M, [&](int lo, int n) {
+        const void *ar = (const char *)a + (size_t)lo * K * e_;
+        void *cr = (char *)c + (size_t)lo * N * e_;
+        hipError_t e;
+        const bool mfma = ctx->cfg.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_GEMM);
+        if (mfma && !(ctx->flags & ISO_FLAG_GEMM_STAGED) && iso_gemm_bf16_dtl_supported(n, N, K))
+            e = iso_launch_gemm_bf16_dtl(ar, w, cr, n, N, K, (ctx->flags >> 8) & 15, sk_for(ctx, s), s);
+        else if (mfma && iso_gemm_bf16_mfma_supported(n, N, K))
+            e = iso_launch_gemm_bf16_mfma(ar, w, cr, n, N, K, s);
+        else
+            e = iso_launch_gemm_simple(ctx->cfg.dtype, ar, w, cr, n, N, K, s);
+        if (e != hipSuccess)
+            return fail(ISO_ERR_HIP, "gemm launch (M=%d N=%d K=%d): %s", n, N, K, hipGetErrorString(e));
+        return (int)ISO_OK;
+    });
 }
 
 int attention(iso_ctx *ctx, const void *q, int q_stride, const void *kc, const void *vc, void *out, int Tc,
@@ -228,8 +248,12 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
                        iso_gemm_swiglu_bf16_supported(ck.n, F, H);
     if (fused) {   // gate/up projection with the activation in its epilogue: the [Tc, 2F] tensor never exists
         Timed t_(ctx, ISO_K_GEMM_GATE_UP, ck.s);
-        hipError_t e_ = iso_launch_gemm_swiglu_bf16(yr, w->w_gate_up, actr, ck.n, F, H, (ctx->flags >> 8) & 15, sk_for(ctx, ck.s), ck.s);
-        if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "gate/up+swiglu launch: %s", hipGetErrorString(e_));
+        ISO_TRY(for_segments(ctx, ck.n, [&](int lo, int n) {
+            hipError_t e_ = iso_launch_gemm_swiglu_bf16(yr + (size_t)lo * H * e, w->w_gate_up, actr + (size_t)lo * F * e, n, F, H,
+                                                        (ctx->flags >> 8) & 15, sk_for(ctx, ck.s), ck.s);
+            if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "gate/up+swiglu launch: %s", hipGetErrorString(e_));
+            return (int)ISO_OK;
+        }));
     } else {
         ISO_TRY(gemm(ctx, ISO_K_GEMM_GATE_UP, yr, w->w_gate_up, gur, ck.n, 2 * F, H, ck.s));
         LAUNCH_TRY(ISO_K_SWIGLU, ck.s, iso_launch_swiglu(c.dtype, gur, actr, ck.n, F, ck.s), "swiglu");
@@ -530,6 +554,19 @@ int iso_destroy(iso_ctx *ctx) {
     if (ctx->rope_sin) (void)hipFree(ctx->rope_sin);
     if (ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
+    return ISO_OK;
+}
+
+int iso_set_gemm_segments(iso_ctx *ctx, int n) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (n < 1 || n > 16) return fail(ISO_ERR_SHAPE, "segments=%d outside [1, 16]", n);
+    ctx->gemm_segments = n;
+    return ISO_OK;
+}
+
+int iso_copy_d2h_async(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src) return fail(ISO_ERR_NULL, "dst and src must be non-NULL");
+    HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, (hipStream_t)stream));
     return ISO_OK;
 }
 

@@ -44,6 +44,7 @@ struct iso_ctx {
     float *x1f;        // [max_seq, hidden] fp32: residual stream between the two blocks of a bf16 layer
     float *rope_cos;   // [max_seq, d/2]
     float *rope_sin;   // [max_seq, d/2]
+    int gemm_segments; // launches per projection GEMM along M (0 or 1: one launch)
     int sk_hold;       // set while a pass enqueues work for which stream-K is not to be picked
     iso_sk_ws sk[2];   // stream-K GEMM workspaces, one per caller stream (bf16 contexts only; base == null otherwise)
     void *host_sink;   // pinned, 2 * max_seq * hidden elements

@@ -108,6 +108,27 @@ def test_full_size_30b_tp4_2k_cost_balanced_chunks_sampled_rows(n_chunks, sched)
         assert orc.max_rel_err(f64(vc)[0], ref["v_cache"]) <= TOL_LAYER[dt]
 
 
+def test_gemm_segmentation_leaves_the_layer_unchanged():
+    """Section 3.2: projections issued as several launches along M.  Each output row depends on its own input row
+    only and the tile kernels' per-row arithmetic does not depend on the row's tile, so the layer output is the
+    same bits for 1, 2 and 3 launches (stream-K off: it would pick a different sum order for different sizes)."""
+    hidden, nq, nkv, d, ffn, T, dt = 1024, 8, 1, 128, 1024, 1536, "bf16"
+    w = [iso.upload_weights(iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=8, dtype=dt), dt)]
+    x = iso_inputs.make_hidden(T, hidden, seed=8, dtype=dt)
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, T) as ctx:
+        ctx.set_flags(iso.ISO_FLAG_NO_STREAMK)
+        outs = []
+        for n_seg in (1, 2, 3):
+            ctx.set_gemm_segments(n_seg)
+            out, _, _ = run_chunks(ctx, w, x, dt, T, [768], nkv, d, T, iso.ISO_COMM_D2H, iso.ISO_SCHED_OVERLAP)
+            outs.append(out.numpy())
+        np.testing.assert_array_equal(outs[1], outs[0])
+        np.testing.assert_array_equal(outs[2], outs[0])
+        with pytest.raises(iso.IsoError) as ei:
+            ctx.set_gemm_segments(0)
+        assert ei.value.code == iso.ISO_ERR_SHAPE
+
+
 def test_chunked_prefill_rejects_bad_arguments():
     wl = iso_inputs.WORKLOADS["tiny_f32"]
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
