@@ -82,6 +82,11 @@ typedef struct {
     const void *w_down;    /* [hidden, ffn]                                                         */
     const void *g_attn;    /* [hidden] RMSNorm gain before the attention block                      */
     const void *g_mlp;     /* [hidden] RMSNorm gain before the MLP block                            */
+    /* Optional FP8 (E4M3) copies of the four matrices, same shapes, one byte per element, each with one fp32
+     * scale per row (= output channel): matrix row = fp8 row * scale.  Made by iso_quantize_rows_fp8.  Read only
+     * when ISO_FLAG_FP8_GEMM is set and all eight pointers are non-NULL; NULL otherwise. */
+    const void *w_qkv_f8, *w_o_f8, *w_gate_up_f8, *w_down_f8;
+    const float *s_qkv, *s_o, *s_gate_up, *s_down;
 } iso_weights;
 
 typedef struct iso_ctx iso_ctx;
@@ -201,10 +206,25 @@ enum {
     ISO_FLAG_GEMM_STAGED = 4, /* register-staged 128x128 MFMA GEMM instead of the direct-to-LDS one */
     ISO_FLAG_NO_FUSE = 8,     /* gate/up projection and SwiGLU as two kernels instead of one        */
     ISO_FLAG_ATTN_STAGED = 16,/* register-staged MFMA attention instead of the direct-to-LDS one    */
-    ISO_FLAG_NO_STREAMK = 32  /* never pick the stream-K launch of the direct-to-LDS GEMM by itself  */
+    ISO_FLAG_NO_STREAMK = 32, /* never pick the stream-K launch of the direct-to-LDS GEMM by itself  */
+    ISO_FLAG_FP8_GEMM = 64    /* bf16 layers: run the four projections on the FP8 matrix cores (needs the FP8
+                                 weights in iso_weights; activations are quantised per token row on the fly) */
     /* bits 8..11: tile variant of the direct-to-LDS GEMM (0 = chosen from the shape) */
 };
 int iso_set_flags(iso_ctx *ctx, int flags);
+
+/* FP8 projections (the paper runs its matrix products in 8 bits, Section 4.1; FP8 E4M3 is the 8-bit type of the
+ * CDNA4 matrix cores).  bf16 contexts only.
+ * iso_quantize_rows_fp8: x [rows, cols] bf16 device -> q [rows, cols] E4M3 bytes + scale [rows] fp32, all device.
+ *   Per row, in fp32: amax = max|x|, q = e4m3(x * (448 / amax)) rounded to nearest even, scale = amax / 448
+ *   (an all-zero row gets scale 1).  cols % 8 == 0.  Used once per weight matrix and, inside the layer, per
+ *   projection input.
+ * iso_gemm_fp8: c [M, N] bf16 = (a8 [M, K] x w8 [N, K]^T) * sa[M] * sw[N], fp32 accumulation of the exact products.
+ *   K % 128 == 0, N % 8 == 0.
+ * Errors: NULL, ISO_ERR_SHAPE for sizes the kernels do not take, ISO_ERR_DTYPE for an fp32 context. */
+int iso_quantize_rows_fp8(iso_ctx *ctx, const void *x, int rows, int cols, void *q, float *scale, void *stream);
+int iso_gemm_fp8(iso_ctx *ctx, const void *a8, const float *sa, const void *w8, const float *sw, void *c,
+                 int M, int N, int K, void *stream);
 
 /* GEMM segmentation (Section 3.2, the remedy for the computation-dominated case): every projection of the layer
  * entry points is issued as n launches over consecutive row ranges (multiples of 256 rows; products with fewer

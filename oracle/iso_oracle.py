@@ -162,6 +162,58 @@ def _comm(p, quant: bool):
     return quant_dequant_rows(p) if quant else p
 
 
+# ----------------------------------------------------------------------------- fp8 projections
+
+FP8_MAX = 448.0          # largest finite value of the 8-bit format below
+
+
+def fp8_e4m3_decode(code) -> np.ndarray:
+    """Value of an OCP FP8 E4M3 byte: 1 sign, 4 exponent (bias 7), 3 mantissa bits; exponent 0 is
+    subnormal (m/8 * 2^-6); S.1111.111 is NaN, there is no infinity, the largest finite value is 448."""
+    code = np.asarray(code, dtype=np.int64)
+    sign = np.where(code & 0x80, -1.0, 1.0)
+    e = (code >> 3) & 0xF
+    m = (code & 7).astype(np.float64)
+    val = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7.0))
+    val = np.where((e == 15) & ((code & 7) == 7), np.nan, val)
+    return sign * val
+
+
+def fp8_e4m3_round(x) -> np.ndarray:
+    """x rounded to the nearest FP8 E4M3 value, ties to the even mantissa, magnitudes above 448 clipped to
+    448.  Returned as float64 values (not codes)."""
+    x = _f64(x)
+    a = np.minimum(np.abs(x), FP8_MAX)
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.clip(e, -6.0, 8.0)                 # below 2^-6 the spacing stays that of the subnormals
+    quantum = 2.0 ** (e - 3.0)
+    return np.sign(x) * np.minimum(np.rint(a / quantum) * quantum, FP8_MAX)
+
+
+def quantize_rows_fp8(a):
+    """Per-row FP8 quantisation of a projection operand (Section 4.1: the paper runs its matrix products in
+    8 bits; this build uses the 8-bit float the target's matrix cores take, with one scale per row).
+    In float32, as the device does it: amax = max|row|, inv = 448 / amax, value = fp8(a * inv),
+    scale = amax / 448 (inv = scale = 1 for an all-zero row).  Returns (fp8 values as float64 [T,K],
+    scales float64 [T]); the represented row is value * scale."""
+    a32 = np.asarray(a, dtype=np.float64).astype(np.float32)
+    amax = np.max(np.abs(a32), axis=-1)
+    nz = amax > 0
+    inv = np.where(nz, np.float32(FP8_MAX) / np.where(nz, amax, np.float32(1)), np.float32(1)).astype(np.float32)
+    scale = np.where(nz, amax / np.float32(FP8_MAX), np.float32(1)).astype(np.float32)
+    scaled = (a32 * inv[..., None]).astype(np.float32)
+    return fp8_e4m3_round(scaled), scale.astype(np.float64)
+
+
+def linear_fp8(a, w) -> np.ndarray:
+    """a w^T with both operands quantised per row to FP8 (rows of w = output channels); exact product of
+    the quantised values, then the two row scales."""
+    aq, sa = quantize_rows_fp8(a)
+    wq, sw = quantize_rows_fp8(w)
+    return (aq @ wq.T) * sa[:, None] * sw[None, :]
+
+
 # ----------------------------------------------------------------------------- layer
 
 def _split_qkv(qkv: np.ndarray, sh: LayerShape):
@@ -173,36 +225,45 @@ def _split_qkv(qkv: np.ndarray, sh: LayerShape):
     return q, k, v
 
 
-def mlp_partial(x1: np.ndarray, w: Dict[str, np.ndarray], sh: LayerShape) -> np.ndarray:
+def _lin(a, w, fp8: bool) -> np.ndarray:
+    """A projection of the layer: exact, or with both operands quantised per row to FP8 (Section 4.1)."""
+    return linear_fp8(a, w) if fp8 else linear(a, w)
+
+
+def mlp_partial(x1: np.ndarray, w: Dict[str, np.ndarray], sh: LayerShape, fp8: bool = False) -> np.ndarray:
     """Row-parallel partial of the MLP block: down(swiglu(gate_up(rmsnorm(x1))))."""
     y2 = rmsnorm(x1, w["g_mlp"], sh.rms_eps)
-    a = swiglu(linear(y2, w["w_gate_up"]))
-    return linear(a, w["w_down"])
+    a = swiglu(_lin(y2, w["w_gate_up"], fp8))
+    return _lin(a, w["w_down"], fp8)
 
 
-def _mlp_block(x1: np.ndarray, w: Dict[str, np.ndarray], sh: LayerShape, quant: bool = False) -> np.ndarray:
-    pm = mlp_partial(x1, w, sh)          # all-reduce over one device = identity
+def _mlp_block(x1: np.ndarray, w: Dict[str, np.ndarray], sh: LayerShape, quant: bool = False,
+               fp8: bool = False) -> np.ndarray:
+    pm = mlp_partial(x1, w, sh, fp8)     # all-reduce over one device = identity
     return x1 + _comm(pm, quant)
 
 
-def layer_unsplit(x, w: Dict[str, np.ndarray], sh: LayerShape, quant: bool = False) -> Dict[str, np.ndarray]:
+def layer_unsplit(x, w: Dict[str, np.ndarray], sh: LayerShape, quant: bool = False,
+                  fp8: bool = False) -> Dict[str, np.ndarray]:
     """One decoder-layer shard over the whole prompt (the pipeline ISO is compared with).
     quant=True sends both partials through the int8 payload of Section 3.2 (per-row quantisation acts on
-    each token separately, so it commutes with the chunking)."""
+    each token separately, so it commutes with the chunking).  fp8=True runs the four projections on
+    operands quantised per row to FP8 (also per token, so it commutes with the chunking too)."""
     x = _f64(x)
     T = x.shape[0]
     pos = np.arange(T)
     y = rmsnorm(x, w["g_attn"], sh.rms_eps)
-    q, k, v = _split_qkv(linear(y, w["w_qkv"]), sh)
+    q, k, v = _split_qkv(_lin(y, w["w_qkv"], fp8), sh)
     q = rope(q, pos, sh.rope_base)
     k = rope(k, pos, sh.rope_base)
     o = attention_full(q, k, v).reshape(T, sh.n_q_heads * sh.head_dim)
-    pa = linear(o, w["w_o"])             # row-parallel partial
+    pa = _lin(o, w["w_o"], fp8)          # row-parallel partial
     x1 = x + _comm(pa, quant)
-    return {"x_out": _mlp_block(x1, w, sh, quant), "k_cache": k, "v_cache": v, "x1": x1, "attn": o, "pa": pa}
+    return {"x_out": _mlp_block(x1, w, sh, quant, fp8), "k_cache": k, "v_cache": v, "x1": x1, "attn": o, "pa": pa}
 
 
-def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split, quant: bool = False) -> Dict[str, np.ndarray]:
+def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split, quant: bool = False,
+              fp8: bool = False) -> Dict[str, np.ndarray]:
     """The same layer as consecutive chunks (Section 3.1: two chunks; Section 6: finer cuts).
 
     `split` is one cut point or an ascending list of cut points strictly inside the prompt.  Chunk c
@@ -223,15 +284,15 @@ def layer_iso(x, w: Dict[str, np.ndarray], sh: LayerShape, split, quant: bool = 
         xc = x[lo:hi]
         pos = np.arange(lo, hi)
         y = rmsnorm(xc, w["g_attn"], sh.rms_eps)
-        q, k, v = _split_qkv(linear(y, w["w_qkv"]), sh)
+        q, k, v = _split_qkv(_lin(y, w["w_qkv"], fp8), sh)
         q = rope(q, pos, sh.rope_base)
         k_cache[lo:hi] = rope(k, pos, sh.rope_base)
         v_cache[lo:hi] = v
         o = attention_chunk(q, k_cache, v_cache, q_offset=lo, kv_len=hi)
-        pa = linear(o.reshape(hi - lo, -1), w["w_o"])
+        pa = _lin(o.reshape(hi - lo, -1), w["w_o"], fp8)
         x1 = xc + _comm(pa, quant)
         x1_all[lo:hi] = x1
-        x_out[lo:hi] = _mlp_block(x1, w, sh, quant)
+        x_out[lo:hi] = _mlp_block(x1, w, sh, quant, fp8)
     return {"x_out": x_out, "k_cache": k_cache, "v_cache": v_cache, "x1": x1_all}
 
 
@@ -258,7 +319,8 @@ def balanced_cuts(sh: LayerShape, T: int, n_chunks: int, attn_flop_cost: float) 
     return np.interp(targets, c, np.arange(T + 1, dtype=np.float64))
 
 
-def layer_rows(x, w: Dict[str, np.ndarray], sh: LayerShape, rows: Sequence[int], quant: bool = False) -> Dict[str, np.ndarray]:
+def layer_rows(x, w: Dict[str, np.ndarray], sh: LayerShape, rows: Sequence[int], quant: bool = False,
+               fp8: bool = False) -> Dict[str, np.ndarray]:
     """Exact output rows `rows` of the layer, without computing the others.
 
     Output row p depends on x[p] and on the K/V rows 0..p only, so K/V are computed
@@ -271,16 +333,16 @@ def layer_rows(x, w: Dict[str, np.ndarray], sh: LayerShape, rows: Sequence[int],
     rows = np.asarray(list(rows), dtype=np.int64)
     y = rmsnorm(x, w["g_attn"], sh.rms_eps)
     w_qkv = _f64(w["w_qkv"])
-    kv = linear(y, w_qkv[nq * d:])
+    kv = _lin(y, w_qkv[nq * d:], fp8)
     k = rope(kv[:, : nkv * d].reshape(T, nkv, d), np.arange(T), sh.rope_base)
     v = kv[:, nkv * d:].reshape(T, nkv, d)
-    q = rope(linear(y[rows], w_qkv[: nq * d]).reshape(len(rows), nq, d), rows, sh.rope_base)
+    q = rope(_lin(y[rows], w_qkv[: nq * d], fp8).reshape(len(rows), nq, d), rows, sh.rope_base)
     o = np.empty((len(rows), nq, d))
     for r, p in enumerate(rows):
         o[r] = attention_chunk(q[r:r + 1], k, v, q_offset=int(p), kv_len=int(p) + 1)[0]
-    pa = linear(o.reshape(len(rows), nq * d), w["w_o"])
+    pa = _lin(o.reshape(len(rows), nq * d), w["w_o"], fp8)
     x1 = x[rows] + _comm(pa, quant)
-    return {"x_out": _mlp_block(x1, w, sh, quant), "k_cache": k, "v_cache": v, "x1": x1, "rows": rows, "pa": pa}
+    return {"x_out": _mlp_block(x1, w, sh, quant, fp8), "k_cache": k, "v_cache": v, "x1": x1, "rows": rows, "pa": pa}
 
 
 # ----------------------------------------------------------------------------- metric

@@ -29,6 +29,7 @@ ISO_SCHED_OVERLAP, ISO_SCHED_SERIAL, ISO_SCHED_STREAM_PER_CHUNK = 0, 1, 2
 ISO_MAX_CHUNKS = 8
 ISO_FLAG_SIMPLE_GEMM, ISO_FLAG_SIMPLE_ATTN, ISO_FLAG_GEMM_STAGED, ISO_FLAG_NO_FUSE, ISO_FLAG_ATTN_STAGED = 1, 2, 4, 8, 16
 ISO_FLAG_NO_STREAMK = 32
+ISO_FLAG_FP8_GEMM = 64
 
 EXPORTS = [
     "iso_validate_cfg", "iso_plan_chunks", "iso_plan_split", "iso_stack_prefill_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",
@@ -36,12 +37,12 @@ EXPORTS = [
     "iso_residual_rmsnorm", "iso_rope_kv_write", "iso_swiglu", "iso_set_flags", "iso_host_sink",
     "iso_timing_enable", "iso_timing_read",
     "iso_device_count", "iso_device_sync", "iso_dev_alloc", "iso_dev_free", "iso_dev_fill", "iso_host_alloc",
-    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2h_async", "iso_set_gemm_segments", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
+    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2h_async", "iso_set_gemm_segments", "iso_quantize_rows_fp8", "iso_gemm_fp8", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
 ]
 KERNEL_KINDS = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn", "rmsnorm", "resid_norm", "residual",
                 "rope_kv", "swiglu", "comm", "quant"]
-DTYPE_BYTES = {"f32": 4, "bf16": 2}
-_NP_STORAGE = {"f32": np.float32, "bf16": np.uint16}
+DTYPE_BYTES = {"f32": 4, "bf16": 2, "u8": 1}
+_NP_STORAGE = {"f32": np.float32, "bf16": np.uint16, "u8": np.uint8}
 
 
 class IsoCfg(ctypes.Structure):
@@ -52,7 +53,10 @@ class IsoCfg(ctypes.Structure):
 
 class IsoWeights(ctypes.Structure):
     _fields_ = [("w_qkv", ctypes.c_void_p), ("w_o", ctypes.c_void_p), ("w_gate_up", ctypes.c_void_p),
-                ("w_down", ctypes.c_void_p), ("g_attn", ctypes.c_void_p), ("g_mlp", ctypes.c_void_p)]
+                ("w_down", ctypes.c_void_p), ("g_attn", ctypes.c_void_p), ("g_mlp", ctypes.c_void_p),
+                ("w_qkv_f8", ctypes.c_void_p), ("w_o_f8", ctypes.c_void_p), ("w_gate_up_f8", ctypes.c_void_p),
+                ("w_down_f8", ctypes.c_void_p), ("s_qkv", ctypes.c_void_p), ("s_o", ctypes.c_void_p),
+                ("s_gate_up", ctypes.c_void_p), ("s_down", ctypes.c_void_p)]
 
 
 class IsoPlan(ctypes.Structure):
@@ -118,6 +122,8 @@ def load() -> ctypes.CDLL:
     lib.iso_copy_d2h.argtypes = [vp, vp, sz]
     lib.iso_copy_d2h_async.argtypes = [vp, vp, sz, vp]
     lib.iso_set_gemm_segments.argtypes = [vp, ci]
+    lib.iso_quantize_rows_fp8.argtypes = [vp, vp, ci, ci, vp, vp, vp]
+    lib.iso_gemm_fp8.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, vp]
     lib.iso_copy_d2d.argtypes = [vp, vp, sz]
     lib.iso_stream_create.argtypes = [pvp]
     lib.iso_stream_destroy.argtypes = [vp]
@@ -310,8 +316,10 @@ def _stream_handle(s) -> Optional[int]:
 
 
 def pack_weights(w: Dict[str, object]) -> IsoWeights:
+    opt = [_ptr(w[k]) if k in w else None
+           for k in ("w_qkv_f8", "w_o_f8", "w_gate_up_f8", "w_down_f8", "s_qkv", "s_o", "s_gate_up", "s_down")]
     return IsoWeights(_ptr(w["w_qkv"]), _ptr(w["w_o"]), _ptr(w["w_gate_up"]), _ptr(w["w_down"]),
-                      _ptr(w["g_attn"]), _ptr(w["g_mlp"]))
+                      _ptr(w["g_attn"]), _ptr(w["g_mlp"]), *opt)
 
 
 def upload_weights(w: Dict[str, np.ndarray], dtype: str) -> Dict[str, DeviceArray]:
@@ -354,6 +362,26 @@ class Context:
     # ---- entry points (same names as the C ABI, without the prefix) ----------------------------
     def sync(self) -> None:
         _check(self._lib.iso_sync(self._h))
+
+    def quantize_rows_fp8(self, x, rows: int, cols: int, q, scale, stream=None) -> None:
+        _check(self._lib.iso_quantize_rows_fp8(self._h, _ptr(x), rows, cols, _ptr(q), _ptr(scale), _stream_handle(stream)))
+
+    def gemm_fp8(self, a8, sa, w8, sw, c, M: int, N: int, K: int, stream=None) -> None:
+        _check(self._lib.iso_gemm_fp8(self._h, _ptr(a8), _ptr(sa), _ptr(w8), _ptr(sw), _ptr(c), M, N, K,
+                                      _stream_handle(stream)))
+
+    def add_fp8_weights(self, w: Dict[str, "DeviceArray"]) -> Dict[str, "DeviceArray"]:
+        """Quantises the four matrices of an uploaded bf16 layer per output row and returns the layer with the
+        FP8 copies and their scales added (what ISO_FLAG_FP8_GEMM reads)."""
+        out = dict(w)
+        for name, sname in (("w_qkv", "s_qkv"), ("w_o", "s_o"), ("w_gate_up", "s_gate_up"), ("w_down", "s_down")):
+            rows, cols = w[name].shape
+            q = DeviceArray((rows, cols), "u8")
+            sc = DeviceArray((rows,), "f32")
+            self.quantize_rows_fp8(w[name], rows, cols, q, sc, self.stream0)
+            out[name + "_f8"], out[sname] = q, sc
+        self.sync()
+        return out
 
     def set_gemm_segments(self, n: int) -> None:
         _check(self._lib.iso_set_gemm_segments(self._h, n))

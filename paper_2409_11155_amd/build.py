@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libiso.so")
 
-SOURCES = ["iso_api.hip", "elementwise.hip", "gemm_simple.hip", "gemm_bf16_mfma.hip", "gemm_bf16_dtl.hip", "attn_simple.hip",
+SOURCES = ["iso_api.hip", "elementwise.hip", "gemm_simple.hip", "gemm_bf16_mfma.hip", "gemm_bf16_dtl.hip", "gemm_fp8_dtl.hip", "attn_simple.hip",
            "attn_bf16_mfma.hip", "attn_bf16_dtl.hip"]
 
 

@@ -40,7 +40,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 int n_qkv(const iso_cfg &c) { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
 
 struct WsLayout {
-    size_t y, qkv, attn, part, gu, act, x1f, q8, total;
+    size_t y, qkv, attn, part, gu, act, x1f, q8, a8, a8s, a8_pitch, total;
 };
 
 WsLayout ws_layout(const iso_cfg &c) {
@@ -56,6 +56,12 @@ WsLayout ws_layout(const iso_cfg &c) {
     l.act = take(t * c.ffn);
     l.x1f = take(c.dtype == ISO_BF16 ? t * c.hidden * 2 : 0);   // fp32 = two bf16 slots per element
     l.q8 = take((t * (c.hidden + 16) + e - 1) / e);
+    size_t kmax = (size_t)c.hidden;
+    if ((size_t)c.n_q_heads * c.head_dim > kmax) kmax = (size_t)c.n_q_heads * c.head_dim;
+    if ((size_t)c.ffn > kmax) kmax = (size_t)c.ffn;
+    l.a8_pitch = kmax;
+    l.a8 = take(c.dtype == ISO_BF16 ? (t * kmax + e - 1) / e : 0);
+    l.a8s = take(c.dtype == ISO_BF16 ? t * 2 : 0);               // fp32 = two bf16 slots
     l.total = off;
     return l;
 }
@@ -121,9 +127,42 @@ template <typename F> int for_segments(const iso_ctx *ctx, int M, F &&launch) {
     return ISO_OK;
 }
 
-int gemm(iso_ctx *ctx, int kind, const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
-    Timed t_(ctx, kind, s);
+#define LAUNCH_TRY(kind, stream, expr, what)                                                       \
+    do {                                                                                           \
+        Timed t_(ctx, kind, stream);                                                               \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "%s launch: %s", what, hipGetErrorString(e_)); \
+    } while (0)
+
+// FP8 operands of one projection of the layer: the FP8 weight and its scales, and the token row the activation
+// rows start at (their FP8 copy goes to that chunk's own region of the workspace).  w8 == NULL: bf16 path.
+struct F8Arg {
+    const void *w8 = nullptr;
+    const float *sw = nullptr;
+    int row0 = 0;
+};
+
+bool use_fp8(const iso_ctx *ctx, const F8Arg &f8, int M, int N, int K) {
+    return (ctx->flags & ISO_FLAG_FP8_GEMM) && ctx->cfg.dtype == ISO_BF16 && f8.w8 && f8.sw &&
+           iso_gemm_fp8_supported(M, N, K);
+}
+
+int gemm(iso_ctx *ctx, int kind, const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s,
+         const F8Arg &f8 = F8Arg()) {
     const size_t e_ = ctx->elt;
+    if (use_fp8(ctx, f8, M, N, K)) {
+        unsigned char *a8 = ctx->a8 + (size_t)f8.row0 * ctx->a8_pitch;
+        float *sa = ctx->a8s + f8.row0;
+        LAUNCH_TRY(ISO_K_QUANT, s, iso_launch_quant_rows_fp8(a, a8, sa, M, K, s), "fp8 row quantiser");
+        Timed t_(ctx, kind, s);
+        return for_segments(ctx, M, [&](int lo, int n) {
+            hipError_t e = iso_launch_gemm_fp8(a8 + (size_t)lo * K, sa + lo, f8.w8, f8.sw, (char *)c + (size_t)lo * N * e_,
+                                               n, N, K, s);
+            if (e != hipSuccess) return fail(ISO_ERR_HIP, "fp8 gemm launch (M=%d N=%d K=%d): %s", n, N, K, hipGetErrorString(e));
+            return (int)ISO_OK;
+        });
+    }
+    Timed t_(ctx, kind, s);
     return for_segments(ctx, M, [&](int lo, int n) {
         const void *ar = (const char *)a + (size_t)lo * K * e_;
         void *cr = (char *)c + (size_t)lo * N * e_;
@@ -163,12 +202,6 @@ int attention(iso_ctx *ctx, const void *q, int q_stride, const void *kc, const v
         if (r_ != ISO_OK) return r_; \
     } while (0)
 
-#define LAUNCH_TRY(kind, stream, expr, what)                                                       \
-    do {                                                                                           \
-        Timed t_(ctx, kind, stream);                                                               \
-        hipError_t e_ = (expr);                                                                    \
-        if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "%s launch: %s", what, hipGetErrorString(e_)); \
-    } while (0)
 
 // Communication point of one chunk: nothing, the [n, H] partial as it is, or its int8 codes + row scales.
 // `which` = 0 after o_proj, 1 after down; the host sink keeps the two points apart.
@@ -211,7 +244,7 @@ int attn_block_head(iso_ctx *ctx, const iso_weights *w, void *x, void *kc, void 
                    at(ctx->part, ck.lo, H, e), xr, w->g_attn, yr, ck.n, H, c.rms_eps, hi, 0, ck.s), "residual+rmsnorm");
     else
         LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, nullptr, nullptr, w->g_attn, yr, ck.n, H, c.rms_eps, 0, 0, ck.s), "rmsnorm");
-    ISO_TRY(gemm(ctx, ISO_K_GEMM_QKV, yr, w->w_qkv, qkvr, ck.n, NQKV, H, ck.s));
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_QKV, yr, w->w_qkv, qkvr, ck.n, NQKV, H, ck.s, F8Arg{w->w_qkv_f8, w->s_qkv, ck.lo}));
     LAUNCH_TRY(ISO_K_ROPE_KV, ck.s, iso_launch_rope_kv(c.dtype, qkvr, kc, vc, ctx->rope_cos, ctx->rope_sin, ck.n, ck.lo, c.n_q_heads,
                                   c.n_kv_heads, c.head_dim, ck.s), "rope+kv");
     return ISO_OK;
@@ -226,7 +259,7 @@ int attn_block_tail(iso_ctx *ctx, const iso_weights *w, void *kc, void *vc, cons
     char *attnr = at(ctx->attn, ck.lo, NQD, e);
     char *partr = at(ctx->part, ck.lo, H, e);
     ISO_TRY(attention(ctx, qkvr, NQKV, kc, vc, attnr, ck.n, ck.lo, ck.lo + ck.n, ck.s));
-    ISO_TRY(gemm(ctx, ISO_K_GEMM_O, attnr, w->w_o, partr, ck.n, H, NQD, ck.s));
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_O, attnr, w->w_o, partr, ck.n, H, NQD, ck.s, F8Arg{w->w_o_f8, w->s_o, ck.lo}));
     if (after_compute) HIP_TRY(hipEventRecord(after_compute, ck.s));
     return comm_point(ctx, comm, 0, ck.lo, ck.n, ck.s);
 }
@@ -246,7 +279,19 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
                w->g_mlp, yr, ck.n, H, c.rms_eps, 0, hi, ck.s), "residual+rmsnorm");
     const bool fused = c.dtype == ISO_BF16 && !(ctx->flags & (ISO_FLAG_SIMPLE_GEMM | ISO_FLAG_GEMM_STAGED | ISO_FLAG_NO_FUSE)) &&
                        iso_gemm_swiglu_bf16_supported(ck.n, F, H);
-    if (fused) {   // gate/up projection with the activation in its epilogue: the [Tc, 2F] tensor never exists
+    const F8Arg f8gu{w->w_gate_up_f8, w->s_gate_up, ck.lo};
+    if (fused && use_fp8(ctx, f8gu, ck.n, 2 * F, H)) {
+        unsigned char *a8 = ctx->a8 + (size_t)ck.lo * ctx->a8_pitch;
+        float *sa = ctx->a8s + ck.lo;
+        LAUNCH_TRY(ISO_K_QUANT, ck.s, iso_launch_quant_rows_fp8(yr, a8, sa, ck.n, H, ck.s), "fp8 row quantiser");
+        Timed t_(ctx, ISO_K_GEMM_GATE_UP, ck.s);
+        ISO_TRY(for_segments(ctx, ck.n, [&](int lo, int n) {
+            hipError_t e_ = iso_launch_gemm_swiglu_fp8(a8 + (size_t)lo * H, sa + lo, f8gu.w8, f8gu.sw, actr + (size_t)lo * F * e,
+                                                       n, F, H, ck.s);
+            if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "fp8 gate/up+swiglu launch: %s", hipGetErrorString(e_));
+            return (int)ISO_OK;
+        }));
+    } else if (fused) {   // gate/up projection with the activation in its epilogue: the [Tc, 2F] tensor never exists
         Timed t_(ctx, ISO_K_GEMM_GATE_UP, ck.s);
         ISO_TRY(for_segments(ctx, ck.n, [&](int lo, int n) {
             hipError_t e_ = iso_launch_gemm_swiglu_bf16(yr + (size_t)lo * H * e, w->w_gate_up, actr + (size_t)lo * F * e, n, F, H,
@@ -255,10 +300,10 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
             return (int)ISO_OK;
         }));
     } else {
-        ISO_TRY(gemm(ctx, ISO_K_GEMM_GATE_UP, yr, w->w_gate_up, gur, ck.n, 2 * F, H, ck.s));
+        ISO_TRY(gemm(ctx, ISO_K_GEMM_GATE_UP, yr, w->w_gate_up, gur, ck.n, 2 * F, H, ck.s, f8gu));
         LAUNCH_TRY(ISO_K_SWIGLU, ck.s, iso_launch_swiglu(c.dtype, gur, actr, ck.n, F, ck.s), "swiglu");
     }
-    ISO_TRY(gemm(ctx, ISO_K_GEMM_DOWN, actr, w->w_down, partr, ck.n, H, F, ck.s));
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_DOWN, actr, w->w_down, partr, ck.n, H, F, ck.s, F8Arg{w->w_down_f8, w->s_down, ck.lo}));
     return comm_point(ctx, comm, 1, ck.lo, ck.n, ck.s);
 }
 
@@ -461,6 +506,9 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
         ctx->part = b + l.part; ctx->gu = b + l.gu; ctx->act = b + l.act;
         ctx->x1f = (float *)(b + l.x1f);
         ctx->q8 = (signed char *)(b + l.q8);
+        ctx->a8 = (unsigned char *)(b + l.a8);
+        ctx->a8s = (float *)(b + l.a8s);
+        ctx->a8_pitch = l.a8_pitch;
         if (!hip_ok(hipMalloc((void **)&ctx->rope_cos, table * sizeof(float)), "hipMalloc(rope cos)")) break;
         if (!hip_ok(hipMalloc((void **)&ctx->rope_sin, table * sizeof(float)), "hipMalloc(rope sin)")) break;
         {   // rotary table: angles in double on the host, stored as fp32
@@ -554,6 +602,28 @@ int iso_destroy(iso_ctx *ctx) {
     if (ctx->rope_sin) (void)hipFree(ctx->rope_sin);
     if (ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
+    return ISO_OK;
+}
+
+int iso_quantize_rows_fp8(iso_ctx *ctx, const void *x, int rows, int cols, void *q, float *scale, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!x || !q || !scale) return fail(ISO_ERR_NULL, "x, q and scale must be non-NULL");
+    if (ctx->cfg.dtype != ISO_BF16) return fail(ISO_ERR_DTYPE, "FP8 quantisation takes bf16 input");
+    if (rows < 1 || cols < 8 || cols % 8) return fail(ISO_ERR_SHAPE, "rows=%d cols=%d: need rows >= 1, cols a positive multiple of 8", rows, cols);
+    hipError_t e = iso_launch_quant_rows_fp8(x, q, scale, rows, cols, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(ISO_ERR_HIP, "fp8 row quantiser launch: %s", hipGetErrorString(e));
+    return ISO_OK;
+}
+
+int iso_gemm_fp8(iso_ctx *ctx, const void *a8, const float *sa, const void *w8, const float *sw, void *c, int M, int N,
+                 int K, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!a8 || !sa || !w8 || !sw || !c) return fail(ISO_ERR_NULL, "operands, scales and c must be non-NULL");
+    if (ctx->cfg.dtype != ISO_BF16) return fail(ISO_ERR_DTYPE, "the FP8 GEMM writes bf16");
+    if (!iso_gemm_fp8_supported(M, N, K)) return fail(ISO_ERR_SHAPE, "M=%d N=%d K=%d: need M >= 1, N %% 8 == 0, K %% 128 == 0", M, N, K);
+    Timed t_(ctx, ISO_K_GEMM_O, (hipStream_t)stream);
+    hipError_t e = iso_launch_gemm_fp8(a8, sa, w8, sw, c, M, N, K, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(ISO_ERR_HIP, "fp8 gemm launch: %s", hipGetErrorString(e));
     return ISO_OK;
 }
 

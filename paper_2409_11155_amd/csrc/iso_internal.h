@@ -42,6 +42,9 @@ struct iso_ctx {
     void *act;         // [max_seq, ffn]
     signed char *q8;   // [max_seq, hidden + 16] int8 codes + fp32 scale per row (ISO_COMM_D2H_INT8)
     float *x1f;        // [max_seq, hidden] fp32: residual stream between the two blocks of a bf16 layer
+    unsigned char *a8; // [max_seq, max(hidden, nq*d, ffn)] FP8 copy of the current projection input (bf16 contexts)
+    float *a8s;        // [max_seq] its row scales
+    size_t a8_pitch;   // bytes per token of a8
     float *rope_cos;   // [max_seq, d/2]
     float *rope_sin;   // [max_seq, d/2]
     int gemm_segments; // launches per projection GEMM along M (0 or 1: one launch)
@@ -76,6 +79,12 @@ hipError_t iso_launch_gemm_swiglu_bf16(const void *a, const void *w, void *act, 
 size_t iso_gemm_sk_ws_bytes(int num_wg);   // device bytes a stream-K workspace for num_wg workgroups needs
 int iso_gemm_sk_max_wg(void);
 bool iso_gemm_swiglu_bf16_supported(int M, int F, int K);
+bool iso_gemm_fp8_supported(int M, int N, int K);
+hipError_t iso_launch_quant_rows_fp8(const void *x, void *q, float *scale, int rows, int cols, hipStream_t s);
+hipError_t iso_launch_gemm_fp8(const void *a8, const float *sa, const void *w8, const float *sw, void *c, int M, int N,
+                               int K, hipStream_t s);
+hipError_t iso_launch_gemm_swiglu_fp8(const void *a8, const float *sa, const void *w8, const float *sw, void *act, int M,
+                                      int F, int K, hipStream_t s);
 hipError_t iso_launch_attn_simple(int dtype, const void *q, const void *k, const void *v, void *out, int Tc,
                                   int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
 hipError_t iso_launch_attn_bf16_mfma(const void *q, const void *k, const void *v, void *out, int Tc,

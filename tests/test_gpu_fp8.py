@@ -1,0 +1,142 @@
+"""GPU parity of the FP8 (E4M3) projections: the row quantiser bit for bit, the FP8 GEMM against the oracle's product
+of the same quantised operands, and the layer with ISO_FLAG_FP8_GEMM against the oracle's FP8 layer."""
+import numpy as np
+import pytest
+
+import paper_2409_11155_amd as iso      # first: binds libiso to the HIP runtime it was built against
+import iso_inputs
+from oracle import iso_oracle as orc
+from test_gpu_parity import (NAN_BYTE, TOL_LAYER, TOL_STEP, dev, f64, h64, make_ctx, oracle_weights, shape_of)
+
+pytestmark = pytest.mark.gpu
+
+# Layer bounds with FP8 projections.  The quantiser is checked bit for bit and the FP8 GEMM to the bf16 step bound
+# on identical inputs (below); at layer level device and oracle quantise activations that differ by the bf16
+# roundings of the device's intermediate tensors (2^-9 relative).  A fraction ~2^-9 / 2^-3.5 of the elements then
+# lands on the other side of an FP8 rounding boundary and moves by one FP8 step (~2^-3.5 of the element), which
+# perturbs a projection output by about sqrt(2^-5.5) * 2^-3.5 = 1.3e-2 of its rms (a numpy emulation of the device
+# pipeline gives 1.26e-2 per projection and 2.1e-2 for the layer).  Four projections in quadrature, with margin:
+TOL_RMS_FP8 = 3e-2
+# The layer metric is a maximum over 1e5..1e7 elements; for errors that are sums of a few one-step flips the maximum
+# sits 6-7 rms above zero (emulation: 6.7), so the bound on max_rel_err is
+TOL_LAYER_FP8 = 0.2
+
+
+def rms_rel_err(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    return float(np.sqrt(np.mean((got - ref) ** 2) / np.mean(ref ** 2)))
+
+
+def test_row_quantiser_matches_the_oracle_bit_for_bit():
+    dt = "bf16"
+    rows, cols = 37, 1000
+    a = iso_inputs.randn((rows, cols), seed=21, dtype=dt)
+    a32 = iso_inputs.bf16_bits_to_f32(a)
+    a32[3] = 0.0                                   # all-zero row
+    a32[5] *= 1e-20                                # tiny row: the scale carries the magnitude
+    a32[7] *= 1e20
+    a32[9, 1:] = 0.0                               # a single non-zero element maps to +-448
+    a = iso_inputs.f32_to_bf16_bits(a32)
+    want_v, want_s = orc.quantize_rows_fp8(h64(a, dt))
+    with make_ctx(256, 4, 4, 64, 64, dt, 256) as ctx:
+        q = iso.DeviceArray((rows, cols), "u8", fill_byte=0x7F)
+        s = iso.DeviceArray((rows,), "f32")
+        ctx.quantize_rows_fp8(dev(a, dt), rows, cols, q, s, ctx.stream0)
+        ctx.sync()
+        got_v = orc.fp8_e4m3_decode(q.numpy())
+        assert not np.isnan(got_v).any()
+        np.testing.assert_array_equal(got_v, want_v)
+        np.testing.assert_array_equal(s.numpy().astype(np.float64), want_s)
+
+
+FP8_GEMM_SHAPES = [(1, 8, 128), (128, 128, 128), (129, 136, 256), (300, 264, 1024), (513, 1280, 2048), (77, 768, 384),
+                   (1024, 4992, 6656), (260, 8, 128)]
+
+
+@pytest.mark.parametrize("M,N,K", FP8_GEMM_SHAPES)
+def test_gemm_fp8(M, N, K):
+    dt = "bf16"
+    a = iso_inputs.randn((M, K), seed=M + N + K, dtype=dt)
+    w = iso_inputs.randn((N, K), seed=M + N + K + 1, dtype=dt, scale=K ** -0.5)
+    with make_ctx(256, 4, 4, 64, 64, dt, 256) as ctx:
+        a8, sa = iso.DeviceArray((M, K), "u8"), iso.DeviceArray((M,), "f32")
+        w8, sw = iso.DeviceArray((N, K), "u8"), iso.DeviceArray((N,), "f32")
+        ctx.quantize_rows_fp8(dev(a, dt), M, K, a8, sa, ctx.stream0)
+        ctx.quantize_rows_fp8(dev(w, dt), N, K, w8, sw, ctx.stream0)
+        c = iso.DeviceArray((M, N), dt, fill_byte=NAN_BYTE)
+        ctx.gemm_fp8(a8, sa, w8, sw, c, M, N, K, ctx.stream0)
+        ctx.sync()
+        ref = orc.linear_fp8(h64(a, dt), h64(w, dt))       # same inputs, same quantiser: only rounding order differs
+        assert orc.max_rel_err(f64(c), ref) <= TOL_STEP[dt]
+
+
+def test_fp8_entry_points_reject_bad_arguments():
+    with make_ctx(256, 4, 4, 64, 64, "bf16", 256) as ctx:
+        a8, s = iso.DeviceArray((8, 128), "u8", fill_byte=0), iso.DeviceArray((8,), "f32", fill_byte=0)
+        c = iso.DeviceArray((8, 8), "bf16", fill_byte=0)
+        for (M, N, K) in ((8, 8, 64), (8, 12, 128), (0, 8, 128)):
+            with pytest.raises(iso.IsoError) as ei:
+                ctx.gemm_fp8(a8, s, a8, s, c, M, N, K, ctx.stream0)
+            assert ei.value.code == iso.ISO_ERR_SHAPE
+        with pytest.raises(iso.IsoError) as ei:
+            ctx.quantize_rows_fp8(c, 8, 12, a8, s, ctx.stream0)
+        assert ei.value.code == iso.ISO_ERR_SHAPE
+    with make_ctx(256, 4, 4, 64, 64, "f32", 256) as ctx:
+        with pytest.raises(iso.IsoError) as ei:
+            ctx.gemm_fp8(a8, s, a8, s, c, 8, 8, 128, ctx.stream0)
+        assert ei.value.code == iso.ISO_ERR_DTYPE
+
+
+@pytest.mark.parametrize("hidden,nq,nkv,ffn,T,splits", [
+    (512, 4, 1, 768, 300, (0, 130)),        # GQA, ragged rows
+    (384, 3, 3, 256, 257, (128,)),          # MHA, odd head count
+])
+def test_small_bf16_layer_with_fp8_projections(hidden, nq, nkv, ffn, T, splits):
+    d, dt = 128, "bf16"
+    w = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=12, dtype=dt)
+    x = iso_inputs.make_hidden(T, hidden, seed=12, dtype=dt)
+    sh = shape_of(hidden, nq, nkv, d, ffn)
+    ref = orc.layer_unsplit(h64(x, dt), oracle_weights(w, dt), sh, fp8=True)
+    exact = orc.layer_unsplit(h64(x, dt), oracle_weights(w, dt), sh)
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, 320) as ctx:
+        w_dev = ctx.add_fp8_weights(iso.upload_weights(w, dt))
+        ctx.set_flags(iso.ISO_FLAG_FP8_GEMM)
+        for split in splits:
+            xd = dev(x, dt)
+            kc = iso.DeviceArray((320, nkv, d), dt, fill_byte=NAN_BYTE)
+            vc = iso.DeviceArray((320, nkv, d), dt, fill_byte=NAN_BYTE)
+            ctx.layer_prefill(w_dev, xd, kc, vc, T, split, iso.ISO_COMM_D2H)
+            ctx.sync()
+            err = orc.max_rel_err(f64(xd), ref["x_out"])
+            assert err <= TOL_LAYER_FP8, (split, err)
+            assert rms_rel_err(f64(xd), ref["x_out"]) <= TOL_RMS_FP8
+            assert orc.max_rel_err(f64(kc)[:T], ref["k_cache"]) <= TOL_LAYER_FP8
+            assert rms_rel_err(f64(kc)[:T], ref["k_cache"]) <= TOL_RMS_FP8
+            # and the FP8 path really ran: the result is further from the exact layer than the bf16 path ever is
+            assert orc.max_rel_err(f64(xd), exact["x_out"]) > TOL_LAYER[dt]
+            print("fp8 layer", hidden, split, "err vs fp8 oracle", err, "rms", rms_rel_err(f64(xd), ref["x_out"]),
+                  "vs exact", orc.max_rel_err(f64(xd), exact["x_out"]))
+
+
+def test_full_size_30b_tp4_2k_fp8_projections_sampled_rows():
+    wl = iso_inputs.WORKLOADS["30b_tp4_2k"]
+    dt = wl.dtype
+    x, w = iso_inputs.make_workload_inputs(wl, seed=0)
+    rows = iso_inputs.sample_rows(wl.seq, wl.split, 48, seed=0)
+    sh = shape_of(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn)
+    ref = orc.layer_rows(h64(x, dt), oracle_weights(w, dt), sh, rows, fp8=True)
+    with make_ctx(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, wl.seq) as ctx:
+        w_dev = ctx.add_fp8_weights(iso.upload_weights(w, dt))
+        ctx.set_flags(iso.ISO_FLAG_FP8_GEMM)
+        for split in (0, wl.split):
+            xd = dev(x, dt)
+            kc = iso.DeviceArray((wl.seq, wl.n_kv_heads, wl.head_dim), dt, fill_byte=NAN_BYTE)
+            vc = iso.DeviceArray((wl.seq, wl.n_kv_heads, wl.head_dim), dt, fill_byte=NAN_BYTE)
+            ctx.layer_prefill(w_dev, xd, kc, vc, wl.seq, split, iso.ISO_COMM_D2H)
+            ctx.sync()
+            err = orc.max_rel_err(f64(xd)[rows], ref["x_out"])
+            print("30b fp8 split", split, "err", err, "rms", rms_rel_err(f64(xd)[rows], ref["x_out"]))
+            assert err <= TOL_LAYER_FP8, (split, err)
+            assert rms_rel_err(f64(xd)[rows], ref["x_out"]) <= TOL_RMS_FP8
+            assert orc.max_rel_err(f64(kc), ref["k_cache"]) <= TOL_LAYER_FP8
+            assert rms_rel_err(f64(kc), ref["k_cache"]) <= TOL_RMS_FP8

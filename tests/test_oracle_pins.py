@@ -453,6 +453,67 @@ def test_quantize_rows_hand_values_and_properties():
     assert np.all(np.abs(orc.quantize_rows(x)[0]).max(axis=1) == 127)
 
 
+def test_fp8_e4m3_format_and_rounding():
+    """The 8-bit float of the FP8 projections, against the format's published definition (OCP FP8 E4M3: bias 7,
+    three mantissa bits, subnormals, no infinity, S.1111.111 = NaN, largest finite 448) and round-to-nearest-even."""
+    v = orc.fp8_e4m3_decode(np.arange(256))
+    assert v[0x00] == 0.0 and v[0x38] == 1.0 and v[0x3C] == 1.5 and v[0x40] == 2.0 and v[0xB8] == -1.0
+    assert v[0x01] == 2.0 ** -9 and v[0x07] == 7 * 2.0 ** -9 and v[0x08] == 2.0 ** -6       # subnormals, first normal
+    assert v[0x7E] == 448.0 and np.isnan(v[0x7F]) and np.isnan(v[0xFF]) and np.nanmax(np.abs(v)) == 448.0
+    pos = v[:0x7F]
+    assert np.all(np.diff(pos) > 0)                                   # codes are ordered like their values
+    fin = v[~np.isnan(v)]
+    np.testing.assert_array_equal(orc.fp8_e4m3_round(fin), fin)       # representable values are fixed points
+    # halfway cases go to the even mantissa; everything else to the nearer neighbour
+    np.testing.assert_array_equal(orc.fp8_e4m3_round([1.0625, 1.1875, 17.0, 19.0, 21.0, 2.0 ** -10, 3 * 2.0 ** -10]),
+                                  [1.0, 1.25, 16.0, 20.0, 20.0, 0.0, 2.0 ** -8])
+    np.testing.assert_array_equal(orc.fp8_e4m3_round([1.06, 1.07, -0.3, 100.0, 447.0, 500.0, -1e9]),
+                                  [1.0, 1.125, -0.3125, 96.0, 448.0, 448.0, -448.0])
+    # brute force: the result is the nearest representable value for a dense sweep
+    xs = np.concatenate([np.linspace(-460, 460, 20011), np.linspace(-0.05, 0.05, 5003)])
+    near = fin[np.argmin(np.abs(xs[:, None] - fin[None, :]), axis=1)]
+    got = orc.fp8_e4m3_round(xs)
+    ties = np.isclose(np.abs(xs - got), np.abs(xs - near), rtol=0, atol=1e-12)
+    assert np.all((got == near) | ties)
+    assert np.all(np.abs(got - xs) <= np.maximum(np.abs(xs), 2.0 ** -6) * 2.0 ** -4 + 1e-12)   # half an ulp, relative
+
+
+def test_fp8_row_quantiser_and_projection():
+    """Per-row scales: the largest element of a row maps to 448, a zero row keeps scale 1, scaling a row by a power
+    of two changes only its scale, and the FP8 projection stays within the format's error of the exact one."""
+    gen = np.random.default_rng(11)
+    a = gen.standard_normal((5, 256))
+    a[3] = 0.0
+    q, s = orc.quantize_rows_fp8(a)
+    assert s[3] == 1.0 and np.all(q[3] == 0.0)
+    for r in (0, 1, 2, 4):
+        assert np.max(np.abs(q[r])) == 448.0
+        assert abs(s[r] - np.max(np.abs(a[r].astype(np.float32))) / 448.0) <= 1e-9
+        assert np.max(np.abs(q[r] * s[r] - a[r])) <= np.max(np.abs(a[r])) * 2.0 ** -4
+    q4, s4 = orc.quantize_rows_fp8(a * 4.0)
+    np.testing.assert_array_equal(q4, q)
+    np.testing.assert_allclose(s4[[0, 1, 2, 4]], 4.0 * s[[0, 1, 2, 4]], rtol=1e-7)
+    w = gen.standard_normal((64, 256)) / 16.0
+    exact, got = orc.linear(a, w), orc.linear_fp8(a, w)
+    # element errors are below 2^-4 relative and independent: the sum over 256 products errs by ~2^-4 * sqrt(2/3) / ...
+    assert 1e-3 < orc.max_rel_err(got, exact) < 0.2
+    np.testing.assert_array_equal(got[3], 0.0)
+    # quantisation is per row on both sides: a subset of rows or channels gives the same numbers
+    np.testing.assert_array_equal(orc.linear_fp8(a[1:3], w[10:20]), got[1:3, 10:20])
+
+
+def test_fp8_layer_stays_split_invariant_and_near_the_exact_layer():
+    wl, x, w, sh = _tiny()
+    exact = orc.layer_unsplit(x, w, sh)
+    ref = orc.layer_unsplit(x, w, sh, fp8=True)
+    assert 1e-3 < orc.max_rel_err(ref["x_out"], exact["x_out"]) < 0.25
+    for cuts in (50, [16, 40, 100]):
+        got = orc.layer_iso(x, w, sh, cuts, fp8=True)
+        assert orc.max_rel_err(got["x_out"], ref["x_out"]) < 1e-12
+    rows = [0, 7, 64, 127]
+    np.testing.assert_allclose(orc.layer_rows(x, w, sh, rows, fp8=True)["x_out"], ref["x_out"][rows], rtol=0, atol=1e-12)
+
+
 def test_quantised_layer_stays_split_invariant_and_close_to_the_exact_layer():
     wl, x, w, sh = _tiny()
     exact = orc.layer_unsplit(x, w, sh)["x_out"]
