@@ -132,6 +132,20 @@ def main() -> int:
     ho = args.headline_only
     if ho:
         return headline_only(t_iso)
+    # the same ISO step timed one at a time (a synchronisation after every step): median and minimum
+    x.copy_from(x0)
+    run(W, split, D2H, OVL)
+    ctx.sync()
+    per_step = []
+    for _ in range(K):
+        iso.device_sync()
+        t0 = time.perf_counter()
+        run(1, split, D2H, OVL)
+        ctx.sync()
+        per_step.append((time.perf_counter() - t0) * 1e3)
+    per_step.sort()
+    t_iso_single = {"median_ms": per_step[len(per_step) // 2], "min_ms": per_step[0], "max_ms": per_step[-1],
+                    "note": "one step per synchronisation; the headline times K steps back to back"}
     t_serial = timed(split, D2H, SER)              # same chunks, one stream: compute + copies back to back
     t_unsplit = timed(0, D2H, SER)                 # the pipeline ISO is compared with
     t_iso_nocomm = timed(split, NONE, OVL)
@@ -263,10 +277,12 @@ def main() -> int:
         for name, fl in gemm_flops_tok.items():
             ms, n = kd[name]
             if n:
-                out[name] = {"ms": ms, "launches": n, "tflops": fl * T / (ms * 1e-3) / 1e12}
+                tf = fl * T / (ms * 1e-3) / 1e12
+                out[name] = {"ms": ms, "launches": n, "tflops": tf, "frac_of_peak": tf / peak}
         ms, n = kd["attn"]
         if n:
-            out["attn"] = {"ms": ms, "launches": n, "tflops": attn_flops / (ms * 1e-3) / 1e12}
+            tf = attn_flops / (ms * 1e-3) / 1e12
+            out["attn"] = {"ms": ms, "launches": n, "tflops": tf, "frac_of_peak": tf / peak}
         for name, b in bytes_tok.items():
             ms, n = kd[name]
             if n:
@@ -276,10 +292,10 @@ def main() -> int:
             out["comm"] = {"ms": ms, "launches": n, "gbs": 2.0 * L * T * H * e / (ms * 1e-3) / 1e9}
         return out
 
-    pk_iso, pk_alone = per_kernel(k_iso), per_kernel(k_alone)
-    gemm_names = list(gemm_flops_tok)
     bf16 = wl.dtype == "bf16"
     peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    pk_iso, pk_alone = per_kernel(k_iso), per_kernel(k_alone)
+    gemm_names = list(gemm_flops_tok)
 
     # ---- roofline of the dominant kernel: the gate/up projection (SwiGLU in its epilogue for bf16) -------
     # one launch per chunk; algorithmic work of a launch = 2 * Tc * 2F * H flops, averaged over the chunks
@@ -314,7 +330,7 @@ def main() -> int:
     sum_c = t_serial - sum_x if t_serial > sum_x else sum(v[0] for k, v in k_alone.items() if k != "comm")
     hideable = min(sum_x, sum_c)
     overlap = {
-        "t_iso_ms": t_iso, "t_split_serial_ms": t_serial, "t_unsplit_ms": t_unsplit,
+        "t_iso_ms": t_iso, "t_iso_single_step": t_iso_single, "t_split_serial_ms": t_serial, "t_unsplit_ms": t_unsplit,
         "t_iso_nocomm_ms": t_iso_nocomm, "t_unsplit_nocomm_ms": t_unsplit_nocomm,
         "reduction_vs_unsplit": 1.0 - t_iso / t_unsplit,
         "iso_over_unsplit": t_iso / t_unsplit,
