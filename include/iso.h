@@ -213,6 +213,20 @@ enum {
 };
 int iso_set_flags(iso_ctx *ctx, int flags);
 
+/* Which kernel a bf16 projection of these sizes takes when nothing is forced, on a device with num_cu compute units
+ * (num_cu == 0: as for a stream the context does not own, i.e. never stream-K).  Host only; for tests and tuning.
+ * kind: ISO_GEMM_TILE_256 / ISO_GEMM_TILE_128 (one 256x256 / 128x128 tile per workgroup, *grid workgroups),
+ * ISO_GEMM_STREAMK (*grid workgroups in teams of *team), ISO_GEMM_STAGED / ISO_GEMM_SIMPLE (the fallbacks for sizes
+ * the direct-to-LDS kernel does not take; *grid is 0).  Errors: NULL, non-positive sizes (ISO_ERR_SHAPE). */
+typedef enum {
+    ISO_GEMM_TILE_256 = 1,
+    ISO_GEMM_TILE_128 = 3,
+    ISO_GEMM_STREAMK = 6,
+    ISO_GEMM_STAGED = 100,
+    ISO_GEMM_SIMPLE = 101
+} iso_gemm_kind;
+int iso_gemm_launch_plan(int M, int N, int K, int num_cu, int *kind, int *team, int *grid);
+
 /* FP8 projections (the paper runs its matrix products in 8 bits, Section 4.1; FP8 E4M3 is the 8-bit type of the
  * CDNA4 matrix cores).  bf16 contexts only.
  * iso_quantize_rows_fp8: x [rows, cols] bf16 device -> q [rows, cols] E4M3 bytes + scale [rows] fp32, all device.

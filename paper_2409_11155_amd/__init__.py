@@ -37,7 +37,7 @@ EXPORTS = [
     "iso_residual_rmsnorm", "iso_rope_kv_write", "iso_swiglu", "iso_set_flags", "iso_host_sink",
     "iso_timing_enable", "iso_timing_read",
     "iso_device_count", "iso_device_sync", "iso_dev_alloc", "iso_dev_free", "iso_dev_fill", "iso_host_alloc",
-    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2h_async", "iso_set_gemm_segments", "iso_quantize_rows_fp8", "iso_gemm_fp8", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
+    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2h_async", "iso_set_gemm_segments", "iso_quantize_rows_fp8", "iso_gemm_fp8", "iso_gemm_launch_plan", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
 ]
 KERNEL_KINDS = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn", "rmsnorm", "resid_norm", "residual",
                 "rope_kv", "swiglu", "comm", "quant"]
@@ -122,6 +122,7 @@ def load() -> ctypes.CDLL:
     lib.iso_copy_d2h.argtypes = [vp, vp, sz]
     lib.iso_copy_d2h_async.argtypes = [vp, vp, sz, vp]
     lib.iso_set_gemm_segments.argtypes = [vp, ci]
+    lib.iso_gemm_launch_plan.argtypes = [ci, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
     lib.iso_quantize_rows_fp8.argtypes = [vp, vp, ci, ci, vp, vp, vp]
     lib.iso_gemm_fp8.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, vp]
     lib.iso_copy_d2d.argtypes = [vp, vp, sz]
@@ -168,6 +169,16 @@ def plan_chunks(cfg: IsoCfg, T: int, split: int) -> IsoPlan:
     plan = IsoPlan()
     _check(load().iso_plan_chunks(ctypes.byref(cfg), T, split, ctypes.byref(plan)))
     return plan
+
+
+ISO_GEMM_TILE_256, ISO_GEMM_TILE_128, ISO_GEMM_STREAMK, ISO_GEMM_STAGED, ISO_GEMM_SIMPLE = 1, 3, 6, 100, 101
+
+
+def gemm_launch_plan(M: int, N: int, K: int, num_cu: int = 256):
+    """(kind, team, grid) of the bf16 projection kernel chosen for these sizes."""
+    kind, team, grid = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(load().iso_gemm_launch_plan(M, N, K, num_cu, ctypes.byref(kind), ctypes.byref(team), ctypes.byref(grid)))
+    return kind.value, team.value, grid.value
 
 
 def plan_split(cfg: IsoCfg, T: int, n_chunks: int, attn_flop_cost: float = 0.0) -> List[int]:

@@ -522,6 +522,27 @@ static bool sk_wanted(int M, int N, int K, const iso_sk_ws *sk) {
     return sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped) >= 40 && grouped;
 }
 
+// What a launch with variant 0 would do on a device with num_wg compute units (host only, no device call).
+// kind: 6 = stream-K (then *team and *grid are its team size and workgroup count), else the tile variant.
+void iso_gemm_bf16_dtl_plan(int M, int N, int K, int num_wg, int *kind, int *team, int *grid) {
+    iso_sk_ws probe;
+    probe.base = &probe;       // non-null: only looked at, never dereferenced
+    probe.err = nullptr;
+    probe.epoch = 0;
+    probe.num_wg = num_wg;
+    int TS = 1, G = 0, grouped = 0;
+    if (num_wg > 0 && sk_wanted(M, N, K, &probe)) {
+        sk_plan(M, N, K, num_wg, &TS, &G, &grouped);
+        *kind = 6;
+    } else {
+        *kind = pick_variant(M, N);
+        const int b = *kind == 1 ? 256 : 128;
+        G = ((M + b - 1) / b) * ((N + b - 1) / b);
+    }
+    *team = TS;
+    *grid = G;
+}
+
 // variant: 0 = pick by shape; 1 = 256x256 8 waves, 2 = 256x128 8 waves, 3 = 128x128 4 waves, 4 = 128x256 8 waves,
 //          5 = 256x256 4 waves, 6 = 256x256 stream-K; +8 selects the plain (non-interleaved) main loop.
 // sk may be null: then the stream-K kernel is not considered (variant 6 is an error).

@@ -605,6 +605,19 @@ int iso_destroy(iso_ctx *ctx) {
     return ISO_OK;
 }
 
+int iso_gemm_launch_plan(int M, int N, int K, int num_cu, int *kind, int *team, int *grid) {
+    if (!kind || !team || !grid) return fail(ISO_ERR_NULL, "kind, team and grid must be non-NULL");
+    if (M < 1 || N < 1 || K < 1 || num_cu < 0) return fail(ISO_ERR_SHAPE, "M=%d N=%d K=%d num_cu=%d", M, N, K, num_cu);
+    if (!iso_gemm_bf16_dtl_supported(M, N, K)) {
+        *kind = iso_gemm_bf16_mfma_supported(M, N, K) ? ISO_GEMM_STAGED : ISO_GEMM_SIMPLE;
+        *team = 1;
+        *grid = 0;
+        return ISO_OK;
+    }
+    iso_gemm_bf16_dtl_plan(M, N, K, num_cu, kind, team, grid);
+    return ISO_OK;
+}
+
 int iso_quantize_rows_fp8(iso_ctx *ctx, const void *x, int rows, int cols, void *q, float *scale, void *stream) {
     if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
     if (!x || !q || !scale) return fail(ISO_ERR_NULL, "x, q and scale must be non-NULL");

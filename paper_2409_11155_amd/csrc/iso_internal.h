@@ -76,6 +76,7 @@ hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M
 bool iso_gemm_bf16_dtl_supported(int M, int N, int K);
 hipError_t iso_launch_gemm_swiglu_bf16(const void *a, const void *w, void *act, int M, int F, int K, int variant,
                                        iso_sk_ws *sk_or_null, hipStream_t s);
+void iso_gemm_bf16_dtl_plan(int M, int N, int K, int num_wg, int *kind, int *team, int *grid);
 size_t iso_gemm_sk_ws_bytes(int num_wg);   // device bytes a stream-K workspace for num_wg workgroups needs
 int iso_gemm_sk_max_wg(void);
 bool iso_gemm_swiglu_bf16_supported(int M, int F, int K);

@@ -91,6 +91,40 @@ def test_plan_split_balances_cost_like_the_oracles_definition():
         assert ei.value.code == code
 
 
+def test_gemm_launch_plan_choices_and_invariants():
+    """Host logic that picks the projection kernel: stream-K only with enough k depth per team, its grid a whole
+    number of teams per XCD and never larger than the device, the team size a divisor of the tile rows."""
+    SK, T256, T128 = iso.ISO_GEMM_STREAMK, iso.ISO_GEMM_TILE_256, iso.ISO_GEMM_TILE_128
+    # the projections of the 30B TP=4 chunk (M = 1024) and of the 70B TP=4 chunk (M = 4096) on 256 compute units
+    assert iso.gemm_launch_plan(1024, 8960, 6656) == (SK, 4, 256)          # gate/up: 35 columns x 104 slices / 64 teams
+    assert iso.gemm_launch_plan(1024, 6656, 1664)[0] == T128               # o_proj: only 10 slices per team
+    assert iso.gemm_launch_plan(1024, 6656, 4480)[0] == T128               # down: 28 slices per team
+    assert iso.gemm_launch_plan(4096, 8192, 7168) == (SK, 8, 256)
+    assert iso.gemm_launch_plan(4096, 8192, 7168, num_cu=0) == (T256, 1, 512)   # no workspace: one tile per workgroup
+    assert iso.gemm_launch_plan(300, 257 * 8, 1000)[0] in (iso.ISO_GEMM_STAGED, iso.ISO_GEMM_SIMPLE)   # K % 64 != 0
+    assert iso.gemm_launch_plan(7, 12, 9)[0] == iso.ISO_GEMM_SIMPLE
+    import random
+    rnd = random.Random(3)
+    for _ in range(3000):
+        M, N, K = rnd.randint(1, 9000), 8 * rnd.randint(1, 2000), 64 * rnd.randint(1, 130)
+        cus = rnd.choice([8, 64, 104, 256, 304])
+        kind, team, grid = iso.gemm_launch_plan(M, N, K, cus)
+        tiles_m, tiles_n, nk = -(-M // 256), -(-N // 256), K // 64
+        if kind == SK:
+            assert team in (1, 2, 4, 8) and tiles_m % team == 0
+            assert 0 < grid <= cus and grid % (8 * team) == 0
+            teams = grid // team
+            assert (tiles_m // team) * tiles_n * nk // teams >= 40
+        elif kind == T256:
+            assert grid == tiles_m * tiles_n and grid >= 128
+        else:
+            assert kind == T128 and grid == (-(-M // 128)) * (-(-N // 128))
+    for args, code in (((0, 8, 64, 256), iso.ISO_ERR_SHAPE), ((8, 8, 64, -1), iso.ISO_ERR_SHAPE)):
+        with pytest.raises(iso.IsoError) as ei:
+            iso.gemm_launch_plan(*args)
+        assert ei.value.code == code
+
+
 def test_null_context_and_null_out_are_refused_without_touching_a_device():
     lib = iso.load()
     w = iso.IsoWeights()
