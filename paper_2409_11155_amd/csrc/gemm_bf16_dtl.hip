@@ -455,9 +455,6 @@ long long sk_plan(int M, int N, int K, int num_wg, int *TS_, int *G_, int *group
     int TS = 1;
     for (int t = 2; t <= 8; t *= 2)
         if (tiles_m % t == 0) TS = t;
-#ifdef ISO_EXP_TS
-    if (getenv("ISO_SK_TS")) TS = atoi(getenv("ISO_SK_TS"));
-#endif
     int G = (num_wg / (8 * TS)) * 8 * TS, grouped = 1;
     long long units = (long long)(tiles_m / TS) * tiles_n * nk;
     if (G < 8 * TS || units < G / TS) {   // tiny problem or odd device
