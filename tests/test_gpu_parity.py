@@ -300,6 +300,38 @@ def test_small_bf16_layer_all_rows(flags, hidden, nq, nkv, ffn, T, splits):
             assert orc.max_rel_err(f64(vc)[:T], ref["v_cache"]) <= TOL_LAYER["bf16"]
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_degenerate_prompts_of_one_two_and_three_tokens(dt):
+    """The shortest prompts: a single token attends to itself only; with two or three tokens every cut leaves
+    one-token chunks."""
+    hidden, nq, nkv, d, ffn = 256, 4, 2, 64, 256
+    w = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=31, dtype=dt)
+    sh = shape_of(hidden, nq, nkv, d, ffn)
+    w_dev = iso.upload_weights(w, dt)
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, 8) as ctx:
+        for T in (1, 2, 3):
+            x = iso_inputs.make_hidden(T, hidden, seed=31 + T, dtype=dt)
+            ref = orc.layer_unsplit(h64(x, dt), oracle_weights(w, dt), sh)
+            for split in range(0, T + 1):
+                out, kc, vc = run_layer(ctx, w_dev, x, dt, T, split, nkv, d, 8, iso.ISO_COMM_D2H, poison=True)
+                assert orc.max_rel_err(f64(out), ref["x_out"]) <= TOL_LAYER[dt], (T, split)
+                assert orc.max_rel_err(f64(kc)[:T], ref["k_cache"]) <= TOL_LAYER[dt]
+                assert np.isnan(f64(kc)[T:]).all()           # rows beyond the prompt are never written
+
+
+def test_small_bf16_layer_with_head_dim_64():
+    """head_dim 64 takes the one-wave-per-row attention kernel inside an otherwise matrix-core layer."""
+    hidden, nq, nkv, d, ffn, T, dt = 512, 8, 2, 64, 640, 200, "bf16"
+    w = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=17, dtype=dt)
+    x = iso_inputs.make_hidden(T, hidden, seed=17, dtype=dt)
+    ref = orc.layer_unsplit(h64(x, dt), oracle_weights(w, dt), shape_of(hidden, nq, nkv, d, ffn))
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, 256) as ctx:
+        for split in (0, 77):
+            out, kc, vc = run_layer(ctx, iso.upload_weights(w, dt), x, dt, T, split, nkv, d, 256, iso.ISO_COMM_D2H, poison=True)
+            assert orc.max_rel_err(f64(out), ref["x_out"]) <= TOL_LAYER[dt], split
+            assert orc.max_rel_err(f64(vc)[:T], ref["v_cache"]) <= TOL_LAYER[dt]
+
+
 def test_two_layer_stack_equals_two_oracle_layers():
     hidden, nq, nkv, d, ffn, T, split, dt = 256, 2, 1, 128, 256, 200, 90, "bf16"
     layers = [iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=20 + l, dtype=dt) for l in range(2)]
