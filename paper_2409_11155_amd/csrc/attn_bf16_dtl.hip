@@ -143,17 +143,33 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
         const unsigned char *kb = lds_g + (jt % NSTAGE) * STAGE_B;
         const unsigned char *vb = kb + TILE_B;
 
-        // --- S^T = K Q^T for two 32-key blocks
+        // --- S^T = K Q^T for two 32-key blocks.  The 16 K fragments are fetched four at a time, one group ahead of
+        //     the MFMAs that use them (left to itself the compiler issues every LDS read right before its MFMA and
+        //     the matrix pipe waits out the LDS latency sixteen times per tile).
         f32x16_t s[2];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
+        {
+            bf16x8_t kf[2][4];
+            auto read_k = [&](int buf, int grp) {          // group = (sub, half of the head dim): 4 k-steps
+                const int sub = grp >> 1, ks0 = (grp & 1) * 4;
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(kb + sub * 32 * ROW_B + k_row_off +
-                                                                         (((2 * ks + lgrp) ^ k_sw) << 4));
-                s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[sub], 0, 0, 0);
+                for (int i = 0; i < 4; ++i)
+                    kf[buf][i] = *reinterpret_cast<const bf16x8_t *>(kb + sub * 32 * ROW_B + k_row_off +
+                                                                    (((2 * (ks0 + i) + lgrp) ^ k_sw) << 4));
+            };
+            read_k(0, 0);
+#pragma unroll
+            for (int grp = 0; grp < 4; ++grp) {
+                if (grp + 1 < 4) read_k((grp + 1) & 1, grp + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                const int sub = grp >> 1, ks0 = (grp & 1) * 4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[grp & 1][i], qf[ks0 + i], s[sub], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         // --- mask (only tiles that touch the diagonal or the end of the cache).  The scores stay unscaled: the
@@ -200,21 +216,31 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
         l_run += psum;
         // --- O^T += V^T P^T.  k-slots 8*lgrp .. +8 of MFMA step (sub, t) hold keys
         //     32 sub + 16 t + 4 lgrp + {0..3} and 32 sub + 16 t + 8 + 4 lgrp + {0..3}: two transposing reads.
+        //     The V fragments of one 32-dim block (4 MFMAs) are fetched while the previous block is multiplied.
+        {
+            bf16x8_t vf[2][4];
+            auto read_v = [&](int buf, int dt) {
+                const int cb = (((4 * dt + v_chunk_base) ^ v_sw) << 4) + v_byte;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) {
-            const int cb = (((4 * dt + v_chunk_base) ^ v_sw) << 4) + v_byte;
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int row = sub * 32 + t * 16 + v_row_base;
+                for (int st = 0; st < 4; ++st) {
+                    const int row = (st >> 1) * 32 + (st & 1) * 16 + v_row_base;
                     const bf16x4_v lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
                         (bf16x4_v __attribute__((address_space(3))) *)(vb + row * ROW_B + cb));
                     const bf16x4_v hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
                         (bf16x4_v __attribute__((address_space(3))) *)(vb + (row + 8) * ROW_B + cb));
-                    const bf16x8_t vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sub][t], o[dt], 0, 0, 0);
+                    vf[buf][st] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 }
+            };
+            read_v(0, 0);
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt) {
+                if (dt + 1 < D / 32) read_v((dt + 1) & 1, dt + 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt & 1][st], pb[st >> 1][st & 1], o[dt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
 
