@@ -227,6 +227,10 @@ def main() -> int:
         ctx.set_flags(args.flags | iso.ISO_FLAG_FP8_GEMM)
         fp8 = {"t_iso_ms": timed(split, D2H, OVL), "t_iso_int8_ms": timed(split, INT8, OVL),
                "t_iso_nocomm_ms": timed(split, NONE, OVL), "t_unsplit_nocomm_ms": timed(0, NONE, SER)}
+        if T >= 768:       # all three remedies of the paper together: 8-bit products, int8 payload, finer cuts
+            b3 = iso.plan_split(cfg, T, 3)
+            fp8["t_iso_int8_3_chunks_ms"] = timed_chunks(b3, INT8, iso.ISO_SCHED_STREAM_PER_CHUNK)
+            fp8["bounds_3_chunks"] = b3
         x.copy_from(x0)
         run(2, split, NONE, SER)
         ctx.sync()
