@@ -122,6 +122,13 @@ int iso_plan_chunks(const iso_cfg *cfg, int T, int split, iso_plan *out);
  * T > max_seq (ISO_ERR_WORKSPACE). */
 int iso_plan_split(const iso_cfg *cfg, int T, int n_chunks, double attn_flop_cost, int *bounds);
 
+/* How many chunks to cut a prompt of T tokens into for ISO_SCHED_STREAM_PER_CHUNK: chunks of about 2048 tokens, at
+ * least 2 and at most ISO_MAX_CHUNKS (1 for prompts shorter than 512 tokens, where the projections of half a prompt no
+ * longer fill the matrix cores).  Rule read off the chunk-count sweeps on MI355X (2k: 2-3, 8k: 4, 32k-128k: 8); more
+ * chunks shorten the unoverlapped ends of the pipeline, fewer keep the GEMMs large.  Host only.
+ * Errors: NULL, bad cfg, T < 1 (ISO_ERR_SHAPE), T > max_seq (ISO_ERR_WORKSPACE). */
+int iso_plan_chunk_count(const iso_cfg *cfg, int T, int *n_chunks);
+
 /* Creates a context on the current HIP device: workspace for max_seq tokens, the rotary table
  * (computed on the host in double, stored fp32), one event pair, and pinned host memory for the
  * copy stand-in.  stream0/stream1 are the caller's two streams (stream1 may equal stream0; NULL is

@@ -32,7 +32,7 @@ ISO_FLAG_NO_STREAMK = 32
 ISO_FLAG_FP8_GEMM = 64
 
 EXPORTS = [
-    "iso_validate_cfg", "iso_plan_chunks", "iso_plan_split", "iso_stack_prefill_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",
+    "iso_validate_cfg", "iso_plan_chunks", "iso_plan_split", "iso_plan_chunk_count", "iso_stack_prefill_chunks", "iso_create", "iso_destroy", "iso_sync", "iso_last_error",
     "iso_layer_prefill", "iso_stack_prefill", "iso_attn_chunk", "iso_gemm_rowpar", "iso_rmsnorm",
     "iso_residual_rmsnorm", "iso_rope_kv_write", "iso_swiglu", "iso_set_flags", "iso_host_sink",
     "iso_timing_enable", "iso_timing_read",
@@ -92,6 +92,7 @@ def load() -> ctypes.CDLL:
     lib.iso_last_error.argtypes = []
     lib.iso_validate_cfg.argtypes = [ctypes.POINTER(IsoCfg)]
     lib.iso_plan_chunks.argtypes = [ctypes.POINTER(IsoCfg), ci, ci, ctypes.POINTER(IsoPlan)]
+    lib.iso_plan_chunk_count.argtypes = [ctypes.POINTER(IsoCfg), ci, ctypes.POINTER(ci)]
     lib.iso_plan_split.argtypes = [ctypes.POINTER(IsoCfg), ci, ci, ctypes.c_double, ctypes.POINTER(ci)]
     lib.iso_create.argtypes = [pvp, ctypes.POINTER(IsoCfg), vp, vp]
     lib.iso_destroy.argtypes = [vp]
@@ -179,6 +180,12 @@ def gemm_launch_plan(M: int, N: int, K: int, num_cu: int = 256):
     kind, team, grid = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     _check(load().iso_gemm_launch_plan(M, N, K, num_cu, ctypes.byref(kind), ctypes.byref(team), ctypes.byref(grid)))
     return kind.value, team.value, grid.value
+
+
+def plan_chunk_count(cfg: IsoCfg, T: int) -> int:
+    n = ctypes.c_int()
+    _check(load().iso_plan_chunk_count(ctypes.byref(cfg), T, ctypes.byref(n)))
+    return n.value
 
 
 def plan_split(cfg: IsoCfg, T: int, n_chunks: int, attn_flop_cost: float = 0.0) -> List[int]:

@@ -444,6 +444,19 @@ int iso_plan_chunks(const iso_cfg *cfg, int T, int split, iso_plan *out) {
     return ISO_OK;
 }
 
+int iso_plan_chunk_count(const iso_cfg *cfg, int T, int *n_chunks) {
+    ISO_TRY(check_cfg(cfg));
+    if (!n_chunks) return fail(ISO_ERR_NULL, "n_chunks is NULL");
+    if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
+    if (T > cfg->max_seq) return fail(ISO_ERR_WORKSPACE, "T=%d exceeds max_seq=%d", T, cfg->max_seq);
+    int n = T / 2048;
+    if (n < 2) n = 2;
+    if (n > ISO_MAX_CHUNKS) n = ISO_MAX_CHUNKS;
+    if (T < 512) n = 1;
+    *n_chunks = n;
+    return ISO_OK;
+}
+
 int iso_plan_split(const iso_cfg *cfg, int T, int n_chunks, double attn_flop_cost, int *bounds) {
     ISO_TRY(check_cfg(cfg));
     if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);

@@ -91,6 +91,19 @@ def test_plan_split_balances_cost_like_the_oracles_definition():
         assert ei.value.code == code
 
 
+def test_plan_chunk_count():
+    cfg = _good_cfg(max_seq=131072, hidden=8192, dtype=iso.ISO_BF16, head_dim=128, n_q_heads=8, n_kv_heads=1, ffn=3584)
+    assert [iso.plan_chunk_count(cfg, T) for T in (1, 511, 512, 2048, 4096, 8192, 16384, 32768, 131072)] == \
+        [1, 1, 2, 2, 2, 4, 8, 8, 8]
+    for T in (512, 3000, 20000, 131072):        # the count always fits the planner and the prompt
+        n = iso.plan_chunk_count(cfg, T)
+        assert 1 <= n <= iso.ISO_MAX_CHUNKS and len(iso.plan_split(cfg, T, n)) == n - 1
+    for T, code in ((0, iso.ISO_ERR_SHAPE), (131073, iso.ISO_ERR_WORKSPACE)):
+        with pytest.raises(iso.IsoError) as ei:
+            iso.plan_chunk_count(cfg, T)
+        assert ei.value.code == code
+
+
 def test_gemm_launch_plan_choices_and_invariants():
     """Host logic that picks the projection kernel: stream-K only with enough k depth per team, its grid a whole
     number of teams per XCD and never larger than the device, the team size a divisor of the tile rows."""
