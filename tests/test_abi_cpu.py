@@ -91,6 +91,13 @@ def test_plan_split_balances_cost_like_the_oracles_definition():
         assert ei.value.code == code
 
 
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+
+
 def test_plan_chunk_count():
     cfg = _good_cfg(max_seq=131072, hidden=8192, dtype=iso.ISO_BF16, head_dim=128, n_q_heads=8, n_kv_heads=1, ffn=3584)
     assert [iso.plan_chunk_count(cfg, T) for T in (1, 511, 512, 2048, 4096, 8192, 16384, 32768, 131072)] == \
