@@ -56,7 +56,9 @@ typedef enum {
 
 /* How the two chunks are issued (Section 1, Figure 1 (a) versus (d)). */
 typedef enum {
-    ISO_SCHED_OVERLAP = 0, /* chunk 0 on stream0, chunk 1 on stream1, one event: KV of chunk 0 written */
+    ISO_SCHED_OVERLAP = 0, /* chunk 0 on stream0, chunk 1 on stream1; one event per layer orders them: with transfers
+                              and chunks of >= 1024 rows chunk 1's attention block starts when chunk 0's has been
+                              issued, otherwise chunk 1's attention starts when chunk 0's K/V rows are written */
     ISO_SCHED_SERIAL = 1,  /* every chunk on stream0, one block after the other, copies in line        */
     ISO_SCHED_STREAM_PER_CHUNK = 2 /* each chunk on a stream of its own (the context makes the extra ones), attention
                                       blocks chained in chunk order; meant for more than two chunks            */

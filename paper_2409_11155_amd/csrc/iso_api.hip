@@ -12,6 +12,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "iso_internal.h"
@@ -371,6 +372,11 @@ int run_stack(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, vo
         ~SkHold() { c->sk_hold = 0; }
     } sk_hold_{ctx};
     ctx->sk_hold = overlap && comm != ISO_COMM_D2H;
+    // With transfers to hide and chunks long enough to fill the chip on their own (measured: from about 1024 rows),
+    // the attention blocks are chained whole; otherwise the chunks' independent front parts run side by side.
+    int min_rows = edges[1] - edges[0];
+    for (int k = 1; k < nc; ++k) min_rows = std::min(min_rows, edges[k + 1] - edges[k]);
+    const bool chain_blocks = overlap && comm != ISO_COMM_NONE && min_rows >= 1024;
     if (overlap) {   // fork: the other streams start after whatever produced x in stream0
         HIP_TRY(hipEventRecord(ctx->ev_fork, st[0]));
         for (int k = 1; k < n_streams; ++k) HIP_TRY(hipStreamWaitEvent(st[k], ctx->ev_fork, 0));
@@ -379,20 +385,30 @@ int run_stack(iso_ctx *ctx, const iso_weights *layers, int n_layers, void *x, vo
         const iso_weights *w = &layers[l];
         void *kc = (char *)k_caches + (size_t)l * cache_bytes;
         void *vc = (char *)v_caches + (size_t)l * cache_bytes;
-        // Heads first: the norm/QKV/RoPE of a chunk do not depend on any other chunk.  A chunk's attention then
-        // waits for an event of its predecessor, and through it for every earlier chunk:
-        //  * two streams: the event says the predecessor's K/V rows are in the cache; the predecessor sits on
-        //    the other stream, behind ITS predecessor's head on this one;
-        //  * one stream per chunk: the event follows the predecessor's output projection, so the attention blocks
-        //    run one after the other in chunk order and the first transfer starts as early as it can, instead of
-        //    all chunks sharing the chip and finishing together.
-        for (int k = 0; k < nc; ++k) {
-            ISO_TRY(attn_block_head(ctx, w, x, kc, vc, ch[k], l > 0));
-            if (overlap && !per_chunk && k + 1 < nc) HIP_TRY(hipEventRecord(ctx->ev_kv[k], ch[k].s));
-        }
-        for (int k = 0; k < nc; ++k) {
-            if (overlap && k > 0) HIP_TRY(hipStreamWaitEvent(ch[k].s, ctx->ev_kv[k - 1], 0));
-            ISO_TRY(attn_block_tail(ctx, w, kc, vc, ch[k], comm, (per_chunk && k + 1 < nc) ? ctx->ev_kv[k] : nullptr));
+        if (chain_blocks) {
+            // Whole attention blocks one after the other in chunk order: chunk k starts once chunk k-1's output
+            // projection has been issued to the matrix cores, so chunk 0 has the chip to itself, its transfer starts
+            // as early as it can and runs under chunk 1's block (the order of the paper's Figure 1(d)).
+            for (int k = 0; k < nc; ++k) {
+                if (k > 0) HIP_TRY(hipStreamWaitEvent(ch[k].s, ctx->ev_kv[k - 1], 0));
+                ISO_TRY(attn_block_head(ctx, w, x, kc, vc, ch[k], l > 0));
+                ISO_TRY(attn_block_tail(ctx, w, kc, vc, ch[k], comm, k + 1 < nc ? ctx->ev_kv[k] : nullptr));
+            }
+        } else {
+            // Heads first: the norm/QKV/RoPE of a chunk do not depend on any other chunk.  A chunk's attention then
+            // waits for an event of its predecessor, and through it for every earlier chunk:
+            //  * two streams: the event says the predecessor's K/V rows are in the cache; the predecessor sits on
+            //    the other stream, behind ITS predecessor's head on this one;
+            //  * one stream per chunk: the event follows the predecessor's output projection, so the attention
+            //    kernels run one after the other in chunk order.
+            for (int k = 0; k < nc; ++k) {
+                ISO_TRY(attn_block_head(ctx, w, x, kc, vc, ch[k], l > 0));
+                if (overlap && !per_chunk && k + 1 < nc) HIP_TRY(hipEventRecord(ctx->ev_kv[k], ch[k].s));
+            }
+            for (int k = 0; k < nc; ++k) {
+                if (overlap && k > 0) HIP_TRY(hipStreamWaitEvent(ch[k].s, ctx->ev_kv[k - 1], 0));
+                ISO_TRY(attn_block_tail(ctx, w, kc, vc, ch[k], comm, (per_chunk && k + 1 < nc) ? ctx->ev_kv[k] : nullptr));
+            }
         }
         for (int k = 0; k < nc; ++k) ISO_TRY(mlp_block(ctx, w, x, ch[k], comm));
     }
