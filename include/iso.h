@@ -244,7 +244,14 @@ int iso_gemm_launch_plan(int M, int N, int K, int num_cu, int *kind, int *team, 
  *   projection input.
  * iso_gemm_fp8: c [M, N] bf16 = (a8 [M, K] x w8 [N, K]^T) * sa[M] * sw[N], fp32 accumulation of the exact products.
  *   K % 128 == 0, N % 8 == 0.
+ * iso_rmsnorm_fp8: the norm in front of an 8-bit projection with the quantiser in its tail.  x [T, hidden] bf16;
+ *   delta (NULL or [T, hidden] bf16): x += delta in place first; then q [T, hidden] / scale [T] are exactly what
+ *   iso_quantize_rows_fp8 gives for the bf16 output of iso_rmsnorm / iso_residual_rmsnorm, which is never stored.
+ *   hidden <= 8192 (the row stays in registers), else ISO_ERR_SHAPE.  The layer entry points use it for the QKV
+ *   and gate/up inputs under ISO_FLAG_FP8_GEMM.
  * Errors: NULL, ISO_ERR_SHAPE for sizes the kernels do not take, ISO_ERR_DTYPE for an fp32 context. */
+int iso_rmsnorm_fp8(iso_ctx *ctx, void *x, const void *delta, const void *g, void *q, float *scale, int T,
+                    void *stream);
 int iso_quantize_rows_fp8(iso_ctx *ctx, const void *x, int rows, int cols, void *q, float *scale, void *stream);
 int iso_gemm_fp8(iso_ctx *ctx, const void *a8, const float *sa, const void *w8, const float *sw, void *c,
                  int M, int N, int K, void *stream);

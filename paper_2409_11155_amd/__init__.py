@@ -37,7 +37,7 @@ EXPORTS = [
     "iso_residual_rmsnorm", "iso_rope_kv_write", "iso_swiglu", "iso_set_flags", "iso_host_sink",
     "iso_timing_enable", "iso_timing_read",
     "iso_device_count", "iso_device_sync", "iso_dev_alloc", "iso_dev_free", "iso_dev_fill", "iso_host_alloc",
-    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2h_async", "iso_set_gemm_segments", "iso_quantize_rows_fp8", "iso_gemm_fp8", "iso_gemm_launch_plan", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
+    "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2h_async", "iso_set_gemm_segments", "iso_quantize_rows_fp8", "iso_rmsnorm_fp8", "iso_gemm_fp8", "iso_gemm_launch_plan", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
 ]
 KERNEL_KINDS = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn", "rmsnorm", "resid_norm", "residual",
                 "rope_kv", "swiglu", "comm", "quant"]
@@ -125,6 +125,7 @@ def load() -> ctypes.CDLL:
     lib.iso_set_gemm_segments.argtypes = [vp, ci]
     lib.iso_gemm_launch_plan.argtypes = [ci, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
     lib.iso_quantize_rows_fp8.argtypes = [vp, vp, ci, ci, vp, vp, vp]
+    lib.iso_rmsnorm_fp8.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp]
     lib.iso_gemm_fp8.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, vp]
     lib.iso_copy_d2d.argtypes = [vp, vp, sz]
     lib.iso_stream_create.argtypes = [pvp]
@@ -383,6 +384,10 @@ class Context:
 
     def quantize_rows_fp8(self, x, rows: int, cols: int, q, scale, stream=None) -> None:
         _check(self._lib.iso_quantize_rows_fp8(self._h, _ptr(x), rows, cols, _ptr(q), _ptr(scale), _stream_handle(stream)))
+
+    def rmsnorm_fp8(self, x, delta, g, q, scale, T: int, stream=None) -> None:
+        _check(self._lib.iso_rmsnorm_fp8(self._h, _ptr(x), _ptr(delta) if delta is not None else None, _ptr(g), _ptr(q),
+                                         _ptr(scale), T, _stream_handle(stream)))
 
     def gemm_fp8(self, a8, sa, w8, sw, c, M: int, N: int, K: int, stream=None) -> None:
         _check(self._lib.iso_gemm_fp8(self._h, _ptr(a8), _ptr(sa), _ptr(w8), _ptr(sw), _ptr(c), M, N, K,

@@ -58,9 +58,16 @@ template <typename T, bool F32> __device__ __forceinline__ void store_vec(void *
 // registers between the reduction and the scaling, so rows up to 256*CACHE*VEC elements are read once.
 // XIN_F32 / XOUT_F32: the residual stream is read from / written to an fp32 side buffer instead of the
 // T-typed one (the bf16 layer keeps its mid-layer residual unrounded between the two blocks).
-template <typename T, bool HAS_DELTA, bool WRITE_Y, bool XIN_F32, bool XOUT_F32>
+//
+// Q8 (bf16 rows of at most 256*CACHE*VEC elements only): instead of y the kernel writes the FP8 (E4M3) codes of
+// y and one fp32 scale per row, exactly as the row quantiser would from the bf16-rounded y: amax = max|y|,
+// code = e4m3(y * (448 / amax)) round to nearest even, scale = amax / 448 (1 for an all-zero row).  The 8-bit
+// projections of the layer (paper Section 4.1) then read their activation operand without a separate pass.
+template <typename T, bool HAS_DELTA, bool WRITE_Y, bool XIN_F32, bool XOUT_F32, bool Q8 = false>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *x, const T *__restrict__ delta, void *x_out,
-                                                      const T *__restrict__ g, T *__restrict__ y, int H, float eps) {
+                                                      const T *__restrict__ g, T *__restrict__ y, int H, float eps,
+                                                      unsigned char *__restrict__ q8 = nullptr,
+                                                      float *__restrict__ q_scale = nullptr) {
     constexpr int VEC = 16 / sizeof(T);
     constexpr int CACHE = 4;
     const int tid = threadIdx.x;
@@ -105,6 +112,46 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *x, const T *__
     __syncthreads();
     const float total = red[0] + red[1] + red[2] + red[3];
     const float scale = 1.0f / sqrtf(total / (float)H + eps);
+
+    if constexpr (Q8) {
+        static_assert(sizeof(T) == 2, "the fused quantiser takes bf16 rows");
+        float amax = 0.f;
+#pragma unroll
+        for (int c = 0; c < CACHE; ++c) {
+            const int idx = tid + c * 256;
+            if (idx < nvec) {
+                float gv[VEC];
+                load16<T>(g + (size_t)idx * VEC, gv);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    vals[c][i] = iso_to_f32(iso_from_f32<T>(vals[c][i] * scale * gv[i]));   // y as bf16 would hold it
+                    amax = fmaxf(amax, fabsf(vals[c][i]));
+                }
+            }
+        }
+        __shared__ float redm[4];
+        amax = iso_wave_max(amax);
+        if ((tid & 63) == 0) redm[tid >> 6] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(redm[0], redm[1]), fmaxf(redm[2], redm[3]));
+        const float inv = amax > 0.f ? 448.0f / amax : 1.0f;
+        if (tid == 0) q_scale[blockIdx.x] = amax > 0.f ? amax / 448.0f : 1.0f;
+#pragma unroll
+        for (int c = 0; c < CACHE; ++c) {
+            const int idx = tid + c * 256;
+            if (idx < nvec) {
+                // the conversion does not saturate; y * inv exceeds 448 by rounding at most
+                auto f = [&](int i) { return fminf(fmaxf(vals[c][i] * inv, -448.0f), 448.0f); };
+                int w0 = 0, w1 = 0;
+                w0 = __builtin_amdgcn_cvt_pk_fp8_f32(f(0), f(1), w0, false);
+                w0 = __builtin_amdgcn_cvt_pk_fp8_f32(f(2), f(3), w0, true);
+                w1 = __builtin_amdgcn_cvt_pk_fp8_f32(f(4), f(5), w1, false);
+                w1 = __builtin_amdgcn_cvt_pk_fp8_f32(f(6), f(7), w1, true);
+                *reinterpret_cast<int2 *>(q8 + row + (size_t)idx * VEC) = make_int2(w0, w1);
+            }
+        }
+        return;
+    }
 
 #pragma unroll
     for (int c = 0; c < CACHE; ++c) {
@@ -276,6 +323,33 @@ hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta, void 
     if (x_in_f32) return rmsnorm_dispatch<bf16_t, true, false>(x, delta, x_out, g, y, T, H, eps, s);
     if (x_out_f32) return rmsnorm_dispatch<bf16_t, false, true>(x, delta, x_out, g, y, T, H, eps, s);
     return rmsnorm_dispatch<bf16_t, false, false>(x, delta, x_out, g, y, T, H, eps, s);
+}
+
+// bf16 only: q8[T, H] / q_scale[T] = FP8 row quantisation of rmsnorm(x (+ delta)) * g; with delta, x_out receives
+// x + delta.  x_in_f32 / x_out_f32 as in iso_launch_rmsnorm.  H <= 8192 (the row stays in registers), H % 8 == 0.
+bool iso_rmsnorm_fp8_supported(int H) { return H >= 8 && H <= 8192 && (H % 8) == 0; }
+
+hipError_t iso_launch_rmsnorm_fp8(const void *x, const void *delta, void *x_out, const void *g, void *q8, float *q_scale,
+                                  int T, int H, float eps, int x_in_f32, int x_out_f32, hipStream_t s) {
+    if (!iso_rmsnorm_fp8_supported(H) || (x_in_f32 && x_out_f32) || ((x_in_f32 || x_out_f32) && !delta))
+        return hipErrorInvalidValue;
+    dim3 grid(T), block(256);
+    const bf16_t *dp = (const bf16_t *)delta, *gp = (const bf16_t *)g;
+    bf16_t *no_y = nullptr;
+    unsigned char *qp = (unsigned char *)q8;
+    if (!delta)
+        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, false, true, false, false, true>), grid, block, 0, s, x, dp, x_out, gp,
+                           no_y, H, eps, qp, q_scale);
+    else if (x_in_f32)
+        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, true, true, true, false, true>), grid, block, 0, s, x, dp, x_out, gp,
+                           no_y, H, eps, qp, q_scale);
+    else if (x_out_f32)
+        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, true, true, false, true, true>), grid, block, 0, s, x, dp, x_out, gp,
+                           no_y, H, eps, qp, q_scale);
+    else
+        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, true, true, false, false, true>), grid, block, 0, s, x, dp, x_out, gp,
+                           no_y, H, eps, qp, q_scale);
+    return hipGetLastError();
 }
 
 hipError_t iso_launch_rope_kv(int dtype, void *qkv, void *k_cache, void *v_cache, const float *cos_t,

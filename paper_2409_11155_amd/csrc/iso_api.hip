@@ -141,6 +141,7 @@ struct F8Arg {
     const void *w8 = nullptr;
     const float *sw = nullptr;
     int row0 = 0;
+    bool prequant = false;   // the producer of the activation has already left its FP8 codes and scales there
 };
 
 bool use_fp8(const iso_ctx *ctx, const F8Arg &f8, int M, int N, int K) {
@@ -154,7 +155,8 @@ int gemm(iso_ctx *ctx, int kind, const void *a, const void *w, void *c, int M, i
     if (use_fp8(ctx, f8, M, N, K)) {
         unsigned char *a8 = ctx->a8 + (size_t)f8.row0 * ctx->a8_pitch;
         float *sa = ctx->a8s + f8.row0;
-        LAUNCH_TRY(ISO_K_QUANT, s, iso_launch_quant_rows_fp8(a, a8, sa, M, K, s), "fp8 row quantiser");
+        if (!f8.prequant)
+            LAUNCH_TRY(ISO_K_QUANT, s, iso_launch_quant_rows_fp8(a, a8, sa, M, K, s), "fp8 row quantiser");
         Timed t_(ctx, kind, s);
         return for_segments(ctx, M, [&](int lo, int n) {
             hipError_t e = iso_launch_gemm_fp8(a8 + (size_t)lo * K, sa + lo, f8.w8, f8.sw, (char *)c + (size_t)lo * N * e_,
@@ -240,12 +242,26 @@ int attn_block_head(iso_ctx *ctx, const iso_weights *w, void *x, void *kc, void 
     char *yr = at(ctx->y, ck.lo, H, e);
     char *qkvr = at(ctx->qkv, ck.lo, NQKV, e);
     const bool hi = c.dtype == ISO_BF16;     // mid-layer residual lives in the fp32 side buffer
-    if (add_prev_partial)   // x = x1 + (previous layer's MLP partial), y = norm(x)
-        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, hi ? (void *)(ctx->x1f + (size_t)ck.lo * H) : (void *)xr,
-                   at(ctx->part, ck.lo, H, e), xr, w->g_attn, yr, ck.n, H, c.rms_eps, hi, 0, ck.s), "residual+rmsnorm");
-    else
+    // 8-bit projection: the norm writes the FP8 codes and row scales of y itself, y is never stored
+    F8Arg f8{w->w_qkv_f8, w->s_qkv, ck.lo};
+    f8.prequant = use_fp8(ctx, f8, ck.n, NQKV, H) && iso_rmsnorm_fp8_supported(H);
+    unsigned char *a8 = ctx->a8 + (size_t)ck.lo * ctx->a8_pitch;
+    float *sa = ctx->a8s + ck.lo;
+    if (add_prev_partial) {   // x = x1 + (previous layer's MLP partial), y = norm(x)
+        void *xin = hi ? (void *)(ctx->x1f + (size_t)ck.lo * H) : (void *)xr;
+        if (f8.prequant)
+            LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm_fp8(xin, at(ctx->part, ck.lo, H, e), xr, w->g_attn, a8, sa, ck.n, H,
+                       c.rms_eps, hi, 0, ck.s), "residual+rmsnorm+fp8");
+        else
+            LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xin, at(ctx->part, ck.lo, H, e), xr, w->g_attn, yr, ck.n, H,
+                       c.rms_eps, hi, 0, ck.s), "residual+rmsnorm");
+    } else if (f8.prequant) {
+        LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm_fp8(xr, nullptr, nullptr, w->g_attn, a8, sa, ck.n, H, c.rms_eps, 0, 0, ck.s),
+                   "rmsnorm+fp8");
+    } else {
         LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, nullptr, nullptr, w->g_attn, yr, ck.n, H, c.rms_eps, 0, 0, ck.s), "rmsnorm");
-    ISO_TRY(gemm(ctx, ISO_K_GEMM_QKV, yr, w->w_qkv, qkvr, ck.n, NQKV, H, ck.s, F8Arg{w->w_qkv_f8, w->s_qkv, ck.lo}));
+    }
+    ISO_TRY(gemm(ctx, ISO_K_GEMM_QKV, yr, w->w_qkv, qkvr, ck.n, NQKV, H, ck.s, f8));
     LAUNCH_TRY(ISO_K_ROPE_KV, ck.s, iso_launch_rope_kv(c.dtype, qkvr, kc, vc, ctx->rope_cos, ctx->rope_sin, ck.n, ck.lo, c.n_q_heads,
                                   c.n_kv_heads, c.head_dim, ck.s), "rope+kv");
     return ISO_OK;
@@ -276,15 +292,23 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
     char *actr = at(ctx->act, ck.lo, F, e);
     const bool hi = c.dtype == ISO_BF16;
     // x1 = x + (attention partial); y = norm(x1).  bf16 layers keep x1 unrounded in the fp32 side buffer.
-    LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, partr, hi ? (void *)(ctx->x1f + (size_t)ck.lo * H) : (void *)xr,
-               w->g_mlp, yr, ck.n, H, c.rms_eps, 0, hi, ck.s), "residual+rmsnorm");
+    // With an 8-bit gate/up projection the norm leaves the FP8 codes and row scales of y instead of y.
+    F8Arg f8gu{w->w_gate_up_f8, w->s_gate_up, ck.lo};
+    f8gu.prequant = use_fp8(ctx, f8gu, ck.n, 2 * F, H) && iso_rmsnorm_fp8_supported(H);
+    unsigned char *a8 = ctx->a8 + (size_t)ck.lo * ctx->a8_pitch;
+    float *sa = ctx->a8s + ck.lo;
+    void *x1 = hi ? (void *)(ctx->x1f + (size_t)ck.lo * H) : (void *)xr;
+    if (f8gu.prequant)
+        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm_fp8(xr, partr, x1, w->g_mlp, a8, sa, ck.n, H, c.rms_eps, 0, hi, ck.s),
+                   "residual+rmsnorm+fp8");
+    else
+        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, partr, x1, w->g_mlp, yr, ck.n, H, c.rms_eps, 0, hi, ck.s),
+                   "residual+rmsnorm");
     const bool fused = c.dtype == ISO_BF16 && !(ctx->flags & (ISO_FLAG_SIMPLE_GEMM | ISO_FLAG_GEMM_STAGED | ISO_FLAG_NO_FUSE)) &&
                        iso_gemm_swiglu_bf16_supported(ck.n, F, H);
-    const F8Arg f8gu{w->w_gate_up_f8, w->s_gate_up, ck.lo};
     if (fused && use_fp8(ctx, f8gu, ck.n, 2 * F, H)) {
-        unsigned char *a8 = ctx->a8 + (size_t)ck.lo * ctx->a8_pitch;
-        float *sa = ctx->a8s + ck.lo;
-        LAUNCH_TRY(ISO_K_QUANT, ck.s, iso_launch_quant_rows_fp8(yr, a8, sa, ck.n, H, ck.s), "fp8 row quantiser");
+        if (!f8gu.prequant)
+            LAUNCH_TRY(ISO_K_QUANT, ck.s, iso_launch_quant_rows_fp8(yr, a8, sa, ck.n, H, ck.s), "fp8 row quantiser");
         Timed t_(ctx, ISO_K_GEMM_GATE_UP, ck.s);
         ISO_TRY(for_segments(ctx, ck.n, [&](int lo, int n) {
             hipError_t e_ = iso_launch_gemm_swiglu_fp8(a8 + (size_t)lo * H, sa + lo, f8gu.w8, f8gu.sw, actr + (size_t)lo * F * e,
@@ -654,6 +678,19 @@ int iso_quantize_rows_fp8(iso_ctx *ctx, const void *x, int rows, int cols, void 
     if (rows < 1 || cols < 8 || cols % 8) return fail(ISO_ERR_SHAPE, "rows=%d cols=%d: need rows >= 1, cols a positive multiple of 8", rows, cols);
     hipError_t e = iso_launch_quant_rows_fp8(x, q, scale, rows, cols, (hipStream_t)stream);
     if (e != hipSuccess) return fail(ISO_ERR_HIP, "fp8 row quantiser launch: %s", hipGetErrorString(e));
+    return ISO_OK;
+}
+
+int iso_rmsnorm_fp8(iso_ctx *ctx, void *x, const void *delta, const void *g, void *q, float *scale, int T, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!x || !g || !q || !scale) return fail(ISO_ERR_NULL, "x, g, q and scale must be non-NULL");
+    if (ctx->cfg.dtype != ISO_BF16) return fail(ISO_ERR_DTYPE, "the fused norm + FP8 quantiser takes bf16 rows");
+    if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
+    if (!iso_rmsnorm_fp8_supported(ctx->cfg.hidden))
+        return fail(ISO_ERR_SHAPE, "hidden=%d: the fused norm + FP8 quantiser takes rows of at most 8192 elements", ctx->cfg.hidden);
+    LAUNCH_TRY(delta ? ISO_K_RESID_NORM : ISO_K_RMSNORM, (hipStream_t)stream,
+               iso_launch_rmsnorm_fp8(x, delta, delta ? x : nullptr, g, q, scale, T, ctx->cfg.hidden, ctx->cfg.rms_eps, 0, 0,
+                                      (hipStream_t)stream), "rmsnorm+fp8");
     return ISO_OK;
 }
 

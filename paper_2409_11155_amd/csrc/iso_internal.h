@@ -81,6 +81,9 @@ size_t iso_gemm_sk_ws_bytes(int num_wg);   // device bytes a stream-K workspace 
 int iso_gemm_sk_max_wg(void);
 bool iso_gemm_swiglu_bf16_supported(int M, int F, int K);
 bool iso_gemm_fp8_supported(int M, int N, int K);
+bool iso_rmsnorm_fp8_supported(int H);
+hipError_t iso_launch_rmsnorm_fp8(const void *x, const void *delta_or_null, void *x_out_or_null, const void *g, void *q8,
+                                  float *q_scale, int T, int H, float eps, int x_in_f32, int x_out_f32, hipStream_t s);
 hipError_t iso_launch_quant_rows_fp8(const void *x, void *q, float *scale, int rows, int cols, hipStream_t s);
 hipError_t iso_launch_gemm_fp8(const void *a8, const float *sa, const void *w8, const float *sw, void *c, int M, int N,
                                int K, hipStream_t s);

@@ -140,3 +140,86 @@ def test_full_size_30b_tp4_2k_fp8_projections_sampled_rows():
             assert rms_rel_err(f64(xd)[rows], ref["x_out"]) <= TOL_RMS_FP8
             assert orc.max_rel_err(f64(kc), ref["k_cache"]) <= TOL_LAYER_FP8
             assert rms_rel_err(f64(kc), ref["k_cache"]) <= TOL_RMS_FP8
+
+
+@pytest.mark.parametrize("hidden", [256, 6656, 8192])
+@pytest.mark.parametrize("with_delta", [False, True])
+def test_norm_with_fp8_tail_equals_norm_then_quantiser(hidden, with_delta):
+    """The fused kernel must leave exactly the codes and scales that the row quantiser derives from the stored bf16
+    norm output (and the same x + delta), and those codes are the oracle quantiser's for that output."""
+    dt, T = "bf16", 37
+    x = iso_inputs.make_hidden(T, hidden, seed=31, dtype=dt)
+    x32 = iso_inputs.bf16_bits_to_f32(x)
+    x32[4] = 0.0                                     # all-zero row: scale 1, codes 0
+    x32[6] *= 1e-12
+    x = iso_inputs.f32_to_bf16_bits(x32)
+    delta = iso_inputs.randn((T, hidden), seed=32, dtype=dt, scale=0.5)
+    if with_delta:
+        d32 = iso_inputs.bf16_bits_to_f32(delta)
+        d32[4] = 0.0
+        delta = iso_inputs.f32_to_bf16_bits(d32)
+    g = iso_inputs.randn((hidden,), seed=33, dtype=dt)
+    with make_ctx(hidden, 2, 1, 128, 256, dt, 64) as ctx:
+        gd = dev(g, dt)
+        # separate kernels
+        x_a, y = dev(x, dt), iso.DeviceArray((T, hidden), dt, fill_byte=NAN_BYTE)
+        if with_delta:
+            ctx.residual_rmsnorm(x_a, dev(delta, dt), gd, y, T, ctx.stream0)
+        else:
+            ctx.rmsnorm(x_a, gd, y, T, ctx.stream0)
+        q_a, s_a = iso.DeviceArray((T, hidden), "u8", fill_byte=0x7F), iso.DeviceArray((T,), "f32")
+        ctx.quantize_rows_fp8(y, T, hidden, q_a, s_a, ctx.stream0)
+        # fused
+        x_b = dev(x, dt)
+        q_b, s_b = iso.DeviceArray((T, hidden), "u8", fill_byte=0x7F), iso.DeviceArray((T,), "f32")
+        ctx.rmsnorm_fp8(x_b, dev(delta, dt) if with_delta else None, gd, q_b, s_b, T, ctx.stream0)
+        ctx.sync()
+        np.testing.assert_array_equal(q_b.numpy(), q_a.numpy())
+        np.testing.assert_array_equal(s_b.numpy(), s_a.numpy())
+        np.testing.assert_array_equal(x_b.numpy(), x_a.numpy())
+        want_v, want_s = orc.quantize_rows_fp8(f64(y))
+        np.testing.assert_array_equal(orc.fp8_e4m3_decode(q_b.numpy()), want_v)
+        np.testing.assert_array_equal(s_b.numpy().astype(np.float64), want_s)
+
+
+def test_norm_with_fp8_tail_rejects_wide_rows_and_fp32():
+    with make_ctx(8320, 2, 1, 128, 256, "bf16", 16) as ctx:
+        x = iso.DeviceArray((4, 8320), "bf16", fill_byte=0)
+        q, s = iso.DeviceArray((4, 8320), "u8"), iso.DeviceArray((4,), "f32")
+        g = iso.DeviceArray((8320,), "bf16", fill_byte=0)
+        with pytest.raises(iso.IsoError) as ei:
+            ctx.rmsnorm_fp8(x, None, g, q, s, 4, ctx.stream0)
+        assert ei.value.code == iso.ISO_ERR_SHAPE
+    with make_ctx(256, 4, 4, 64, 64, "f32", 16) as ctx:
+        x = iso.DeviceArray((4, 256), "f32", fill_byte=0)
+        q, s = iso.DeviceArray((4, 256), "u8"), iso.DeviceArray((4,), "f32")
+        g = iso.DeviceArray((256,), "f32", fill_byte=0)
+        with pytest.raises(iso.IsoError) as ei:
+            ctx.rmsnorm_fp8(x, None, g, q, s, 4, ctx.stream0)
+        assert ei.value.code == iso.ISO_ERR_DTYPE
+
+
+def test_two_layer_stack_with_fp8_projections():
+    """Layer 2's first norm takes the residual from the fp32 side buffer: that variant of the fused norm + quantiser
+    only runs inside a stack."""
+    hidden, nq, nkv, d, ffn, T, dt = 512, 4, 1, 128, 768, 300, "bf16"
+    layers = [iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=40 + l, dtype=dt) for l in range(2)]
+    x = iso_inputs.make_hidden(T, hidden, seed=6, dtype=dt)
+    sh = shape_of(hidden, nq, nkv, d, ffn)
+    ref = h64(x, dt)
+    for w in layers:
+        ref = orc.layer_unsplit(ref, oracle_weights(w, dt), sh, fp8=True)["x_out"]
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, 320) as ctx:
+        layers_dev = [ctx.add_fp8_weights(iso.upload_weights(w, dt)) for w in layers]
+        ctx.set_flags(iso.ISO_FLAG_FP8_GEMM)
+        outs = []
+        for split in (0, 130):
+            xd = dev(x, dt)
+            kcs = iso.DeviceArray((2, 320, nkv, d), dt, fill_byte=NAN_BYTE)
+            vcs = iso.DeviceArray((2, 320, nkv, d), dt, fill_byte=NAN_BYTE)
+            ctx.stack_prefill(layers_dev, xd, kcs, vcs, T, split, iso.ISO_COMM_D2H)
+            ctx.sync()
+            err, rms = orc.max_rel_err(f64(xd), ref), rms_rel_err(f64(xd), ref)
+            print("fp8 stack split", split, "err", err, "rms", rms)
+            assert err <= 2 * TOL_LAYER_FP8 and rms <= 2 * TOL_RMS_FP8
+            outs.append(xd.numpy())
