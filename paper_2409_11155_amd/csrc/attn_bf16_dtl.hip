@@ -15,6 +15,7 @@
 //     i.e. each lane gets 4 consecutive keys of one dim -- the k-contiguous operand layout the MFMA wants
 //     for V^T -- with no transposing pass over V anywhere.
 #include "iso_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -26,6 +27,31 @@ constexpr int TILE_B = BN * ROW_B; // 16 KB
 constexpr int STAGE_B = 2 * TILE_B;
 
 typedef __bf16 bf16x4_v __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2_v __attribute__((ext_vector_type(2)));
+
+// Transposing LDS read (ds_read_b64_tr_b16) at LDS byte address `addr` + OFF, written as an instruction: the
+// compiler treats the intrinsic form as possibly aliasing the global -> LDS loads in flight and puts a wait for all
+// of them (the NEXT tile's loads) in front of it, which serialises the prefetch with the second product.  The data
+// being read was landed and fenced by the barrier at the top of the tile loop.  The compiler does not track the
+// completion of these reads either: lds_tr_wait<N>() is the matching s_waitcnt, tied to the registers it guards.
+template <int OFF> __device__ __forceinline__ bf16x4_v lds_read_tr16(uint32_t addr) {
+    bf16x4_v r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+// Waits until at most N LDS reads issued later than the guarded ones are outstanding (LDS reads complete in order).
+template <int N> __device__ __forceinline__ void lds_tr_wait(bf16x8_t &a, bf16x8_t &b, bf16x8_t &c, bf16x8_t &d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+
+// max of a value with the one held by the lane 32 places away (the other half of the wave): v_permlane32_swap
+// exchanges the upper half of its first operand with the lower half of its second, so with both operands equal the
+// two results hold {low, low} and {high, high}; no LDS round trip as a lane shuffle would take.
+__device__ __forceinline__ float half_swap_max(float v) {
+    const unsigned u = __float_as_uint(v);
+    const u32x2_v r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 // NSTAGE LDS stages per group of four waves: tile j + NSTAGE - 1 is requested while tile j is multiplied.  Two stages
 // (64 KB) let two workgroups share a compute unit and hide each other's latency.
@@ -45,9 +71,12 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = (tid >> 6) & 3;                    // wave inside its group of four: owns 32 query rows
-    const int kgrp = KVS == 1 ? 0 : (tid >> 8);         // which part of the key tiles this group of waves takes
+    // wave-uniform values are made scalar explicitly: LDS bases of the wave-loads, the diagonal tests and the mask
+    // branch then cost scalar instructions instead of per-lane compares and exec-mask juggling
+    const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave inside its group of four: 32 query rows
+    const int kgrp = KVS == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 8);   // which part of the key tiles
     unsigned char *const lds_g = lds + kgrp * (NSTAGE * STAGE_B);
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_g;
     const int lcol = lane & 31, lgrp = lane >> 5;
     const int n_tiles_m = (Tc + BM - 1) / BM;
     const int tile_m = n_tiles_m - 1 - blockIdx.x;      // longest rows first
@@ -128,7 +157,13 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
 #pragma unroll
     for (int p = 0; p < NSTAGE - 1; ++p)
         if (p < n_tiles) issue(p, (t_lo + p) * BN);
-    for (int jt = 0; jt < n_iter; ++jt) {
+    // Tiles that lie entirely at or below the diagonal of the block's first row and inside the cache need neither
+    // a mask nor a per-wave skip: they run a branch-free body.  The few tiles that touch the diagonal or the end of
+    // the cache (and the idle iterations of the shorter key group) take the general body.
+    const int n_plain_all = min((q_offset + m0 + 1) / BN, kv_len / BN);
+    const int n_main = max(0, min(n_plain_all - t_lo, n_tiles));
+    auto tile = [&](int jt, auto tail_c) {
+        constexpr bool TAIL = decltype(tail_c)::value;
         const int j0 = (t_lo + jt) * BN;
         // this wave's loads of tile jt have landed: in steady state the NSTAGE-2 younger tiles (8 loads each)
         // may still be in flight; near the end fewer are outstanding, so wait for everything
@@ -138,10 +173,11 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
             __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();                    // ... everyone's have, and tile jt-1 is no longer being read
         if (jt + NSTAGE - 1 < n_tiles) issue((jt + NSTAGE - 1) % NSTAGE, j0 + (NSTAGE - 1) * BN);
-        if (KVS > 1 && jt >= n_tiles) continue;   // the shorter group idles through the last barrier
-        if (j0 > wave_q_max) continue;      // every key of this tile is above this wave's diagonal
+        if (TAIL) {
+            if (KVS > 1 && jt >= n_tiles) return;   // the shorter group idles through the last barrier
+            if (j0 > wave_q_max) return;            // every key of this tile is above this wave's diagonal
+        }
         const unsigned char *kb = lds_g + (jt % NSTAGE) * STAGE_B;
-        const unsigned char *vb = kb + TILE_B;
 
         // --- S^T = K Q^T for two 32-key blocks.  The 16 K fragments are fetched four at a time, one group ahead of
         //     the MFMAs that use them (left to itself the compiler issues every LDS read right before its MFMA and
@@ -175,21 +211,21 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
         // --- mask (only tiles that touch the diagonal or the end of the cache).  The scores stay unscaled: the
         //     softmax scale is positive, so the running maximum can be kept in raw units and the scale folded
         //     into the exponent's multiply-add.
-        const bool need_mask = (j0 + BN - 1 > q_offset + m0 + wave * 32) || (j0 + BN > kv_len);
+        if (TAIL && ((j0 + BN - 1 > q_offset + m0 + wave * 32) || (j0 + BN > kv_len))) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = j0 + sub * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4);
+                    if (key > q_abs || key >= kv_len) s[sub][r] = -INFINITY;
+                }
+        }
         float mx = -INFINITY;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float v = s[sub][r];
-                if (need_mask) {
-                    const int key = j0 + sub * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4);
-                    if (key > q_abs || key >= kv_len) v = -INFINITY;
-                    s[sub][r] = v;
-                }
-                mx = fmaxf(mx, v);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
+        mx = half_swap_max(mx);
         const float m_new = fmaxf(m_run, mx);
         const float neg_m = -m_new * sc;
         float psum = 0.f;
@@ -219,30 +255,35 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
         //     The V fragments of one 32-dim block (4 MFMAs) are fetched while the previous block is multiplied.
         {
             bf16x8_t vf[2][4];
+            const uint32_t vb_addr = lds_addr + (uint32_t)((jt % NSTAGE) * STAGE_B + TILE_B + v_row_base * ROW_B + v_byte);
             auto read_v = [&](int buf, int dt) {
-                const int cb = (((4 * dt + v_chunk_base) ^ v_sw) << 4) + v_byte;
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    const int row = (st >> 1) * 32 + (st & 1) * 16 + v_row_base;
-                    const bf16x4_v lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                        (bf16x4_v __attribute__((address_space(3))) *)(vb + row * ROW_B + cb));
-                    const bf16x4_v hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                        (bf16x4_v __attribute__((address_space(3))) *)(vb + (row + 8) * ROW_B + cb));
-                    vf[buf][st] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
+                const uint32_t a = vb_addr + (uint32_t)(((4 * dt + v_chunk_base) ^ v_sw) << 4);
+                // MFMA step st = (sub, t) takes key rows 32 sub + 16 t + {0, 8} (+ the lane's row inside the block)
+                vf[buf][0] = __builtin_shufflevector(lds_read_tr16<0 * ROW_B>(a), lds_read_tr16<8 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+                vf[buf][1] = __builtin_shufflevector(lds_read_tr16<16 * ROW_B>(a), lds_read_tr16<24 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+                vf[buf][2] = __builtin_shufflevector(lds_read_tr16<32 * ROW_B>(a), lds_read_tr16<40 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+                vf[buf][3] = __builtin_shufflevector(lds_read_tr16<48 * ROW_B>(a), lds_read_tr16<56 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
             };
             read_v(0, 0);
 #pragma unroll
             for (int dt = 0; dt < D / 32; ++dt) {
-                if (dt + 1 < D / 32) read_v((dt + 1) & 1, dt + 1);
-                __builtin_amdgcn_sched_barrier(0);
+                if (dt + 1 < D / 32) {
+                    read_v((dt + 1) & 1, dt + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    lds_tr_wait<8>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);   // 8 younger reads may pend
+                } else {
+                    __builtin_amdgcn_sched_barrier(0);
+                    lds_tr_wait<0>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);
+                }
 #pragma unroll
                 for (int st = 0; st < 4; ++st)
                     o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt & 1][st], pb[st >> 1][st & 1], o[dt], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-    }
+    };
+    for (int jt = 0; jt < n_main; ++jt) tile(jt, std::false_type{});
+    for (int jt = n_main; jt < n_iter; ++jt) tile(jt, std::true_type{});
 
     if (KVS > 1) {
         // merge the two groups: group 1 parks (m, l, o) of its rows in LDS, group 0 folds them into its own.
