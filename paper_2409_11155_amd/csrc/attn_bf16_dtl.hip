@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
                                                             const bf16_t *__restrict__ Kc,
                                                             const bf16_t *__restrict__ Vc,
                                                             bf16_t *__restrict__ Out, int Tc, int q_offset,
-                                                            int kv_len, int nq, int nkv, int q_stride) {
+                                                            int kv_len, int nq, int nkv, int q_stride, int pair) {
 #if defined(__HIP_DEVICE_COMPILE__)
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
@@ -79,7 +79,15 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
     const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_g;
     const int lcol = lane & 31, lgrp = lane >> 5;
     const int n_tiles_m = (Tc + BM - 1) / BM;
-    const int tile_m = n_tiles_m - 1 - blockIdx.x;      // longest rows first
+    // pair != 0: the workgroup takes row block n-1-x and then row block x.  The causal work of a row block grows
+    // linearly with its index, so every workgroup of the launch then has the same amount of work; with one row
+    // block each, a launch of about as many workgroups as the chip holds at once ends when its longest one does,
+    // with most compute units idle by then.
+    const int n_pass = (pair && (int)blockIdx.x != n_tiles_m - 1 - (int)blockIdx.x) ? 2 : 1;
+#pragma nounroll
+    for (int pass = 0; pass < n_pass; ++pass) {
+    if (pass) __syncthreads();                          // the merge of the previous row block is done with the LDS
+    const int tile_m = pass ? (int)blockIdx.x : n_tiles_m - 1 - (int)blockIdx.x;      // longest rows first
     const int h = blockIdx.y;
     const int g = h / (nq / nkv);
     const int m0 = tile_m * BM;
@@ -87,6 +95,7 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
     // ---- this wave's 32 query rows as the B operand (k = head dim): 8 k-steps of 16
     const int q_row = min(m0 + wave * 32 + lcol, Tc - 1);
     const int q_abs = q_offset + m0 + wave * 32 + lcol;
+    const int wave_q_max = q_offset + m0 + wave * 32 + 31;
     bf16x8_t qf[D / 16];
     {
         const bf16_t *qp = Q + (size_t)q_row * q_stride + (size_t)h * D + lgrp * 8;
@@ -94,18 +103,7 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
         for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t *>(qp + ks * 16);
     }
 
-    // ---- this group's share of the key tiles: [t_lo, t_lo + n_tiles); with KVS == 2 the first group takes the larger
-    //      half and both groups run n_iter iterations so that they meet at every barrier
-    const int kv_end = min(kv_len, q_offset + min(m0 + BM, Tc));    // exclusive
-    const int n_tiles_all = (kv_end + BN - 1) / BN;
-    const int half = (n_tiles_all + KVS - 1) / KVS;
-    const int t_lo = kgrp * half;
-    const int n_tiles = max(0, min(half, n_tiles_all - t_lo));
-    const int n_iter = KVS == 1 ? n_tiles : half;
-
-    // ---- direct-to-LDS loads: wave-load = 4 rows x 256 B; lane = (row l/16, slot l%16).  Tile t of the group lives in
-    //      stage t % 2 (K in the first 16 KB, V in the second); K and V are requested separately because the K tile is
-    //      needed one iteration before the V tile (see the loop below).
+    // ---- direct-to-LDS loads: wave-load = 4 rows x 256 B; lane = (row l/16, slot l%16)
     const uint32_t row_stride = (uint32_t)nkv * D * 2u;                         // bytes between cache rows
     const uint32_t n_rec = (uint32_t)(kv_len - 1) * row_stride + (uint32_t)ROW_B;  // this head's slice, rows < kv_len
     const __amdgpu_buffer_rsrc_t rs_k =
@@ -120,37 +118,19 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
         k_off[i] = (uint32_t)r * row_stride + (uint32_t)((slot ^ (r & 15)) << 4);
         v_off[i] = (uint32_t)r * row_stride + (uint32_t)((slot ^ ((r & 3) << 2)) << 4);
     }
-    auto issue_k = [&](int t) {
-        unsigned char *base = lds_g + (t & 1) * STAGE_B;
-        const uint32_t tile_off = (uint32_t)((t_lo + t) * BN) * row_stride;
+    auto issue = [&](int stage, int j0) {
+        unsigned char *base = lds_g + stage * STAGE_B;
+        const uint32_t tile_off = (uint32_t)j0 * row_stride;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rs_k, (__attribute__((address_space(3))) void *)(base + (wave + 4 * i) * 1024), 16, k_off[i] + tile_off, 0,
                 0, 0);
-    };
-    // one of the eight requests of iteration t's prefetch: i < 4 -> K(t+2), else V(t+1)
-    auto issue_one = [&](int t, int i) {
-        if (i < 4) {
-            unsigned char *base = lds_g + (t & 1) * STAGE_B;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_k, (__attribute__((address_space(3))) void *)(base + (wave + 4 * i) * 1024), 16,
-                k_off[i] + (uint32_t)((t_lo + t + 2) * BN) * row_stride, 0, 0, 0);
-        } else {
-            unsigned char *base = lds_g + ((t + 1) & 1) * STAGE_B + TILE_B;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_v, (__attribute__((address_space(3))) void *)(base + (wave + 4 * (i - 4)) * 1024), 16,
-                v_off[i - 4] + (uint32_t)((t_lo + t + 1) * BN) * row_stride, 0, 0, 0);
-        }
-    };
-    auto issue_v = [&](int t) {
-        unsigned char *base = lds_g + (t & 1) * STAGE_B + TILE_B;
-        const uint32_t tile_off = (uint32_t)((t_lo + t) * BN) * row_stride;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_v, (__attribute__((address_space(3))) void *)(base + (wave + 4 * i) * 1024), 16, v_off[i] + tile_off, 0,
-                0, 0);
+                rs_v, (__attribute__((address_space(3))) void *)(base + TILE_B + (wave + 4 * i) * 1024), 16,
+                v_off[i] + tile_off, 0, 0, 0);
     };
 
     // ---- LDS read addressing
@@ -173,42 +153,73 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
     float l_run = 0.f;
     const float sc = 1.4426950408889634f / sqrtf((float)D);
 
-    // K fragment idx = 8 * (32-key block) + k-step of tile t
-    auto k_frag = [&](const unsigned char *kb, int idx) {
-        const int sub = idx >> 3, ks = idx & 7;
-        return *reinterpret_cast<const bf16x8_t *>(kb + sub * 32 * ROW_B + k_row_off + (((2 * ks + lgrp) ^ k_sw) << 4));
-    };
-    // S^T = K Q^T of tile t for two 32-key blocks, on its own.  The 16 K fragments are fetched four at a time, one
-    // group ahead of the MFMAs that use them.
-    auto qk_plain = [&](int t, f32x16_t (&s)[2]) {
-        const unsigned char *kb = lds_g + (t & 1) * STAGE_B;
+    const int kv_end = min(kv_len, q_offset + min(m0 + BM, Tc));    // exclusive
+    const int n_tiles_all = (kv_end + BN - 1) / BN;
+    // this group's tiles [t_lo, t_lo + n_tiles); with KVS == 2 the first group takes the larger half and both groups
+    // run the loop n_iter times so that they meet at every barrier
+    const int half = (n_tiles_all + KVS - 1) / KVS;
+    const int t_lo = kgrp * half;
+    const int n_tiles = max(0, min(half, n_tiles_all - t_lo));
+    const int n_iter = KVS == 1 ? n_tiles : half;
+
+#pragma unroll
+    for (int p = 0; p < NSTAGE - 1; ++p)
+        if (p < n_tiles) issue(p, (t_lo + p) * BN);
+    // Tiles that lie entirely at or below the diagonal of the block's first row and inside the cache need neither
+    // a mask nor a per-wave skip: they run a branch-free body.  The few tiles that touch the diagonal or the end of
+    // the cache (and the idle iterations of the shorter key group) take the general body.
+    const int n_plain_all = min((q_offset + m0 + 1) / BN, kv_len / BN);
+    const int n_main = max(0, min(n_plain_all - t_lo, n_tiles));
+    auto tile = [&](int jt, auto tail_c) {
+        constexpr bool TAIL = decltype(tail_c)::value;
+        const int j0 = (t_lo + jt) * BN;
+        // this wave's loads of tile jt have landed: in steady state the NSTAGE-2 younger tiles (8 loads each)
+        // may still be in flight; near the end fewer are outstanding, so wait for everything
+        if (NSTAGE > 2 && jt + NSTAGE - 2 < n_tiles)
+            __builtin_amdgcn_s_waitcnt(0x0F70 | ((8 * (NSTAGE - 2)) & 15) | (((8 * (NSTAGE - 2)) >> 4) << 14));
+        else
+            __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();                    // ... everyone's have, and tile jt-1 is no longer being read
+        if (jt + NSTAGE - 1 < n_tiles) issue((jt + NSTAGE - 1) % NSTAGE, j0 + (NSTAGE - 1) * BN);
+        if (TAIL) {
+            if (KVS > 1 && jt >= n_tiles) return;   // the shorter group idles through the last barrier
+            if (j0 > wave_q_max) return;            // every key of this tile is above this wave's diagonal
+        }
+        const unsigned char *kb = lds_g + (jt % NSTAGE) * STAGE_B;
+
+        // --- S^T = K Q^T for two 32-key blocks.  The 16 K fragments are fetched four at a time, one group ahead of
+        //     the MFMAs that use them (left to itself the compiler issues every LDS read right before its MFMA and
+        //     the matrix pipe waits out the LDS latency sixteen times per tile).
+        f32x16_t s[2];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
-        bf16x8_t kf[2][4];
+        {
+            bf16x8_t kf[2][4];
+            auto read_k = [&](int buf, int grp) {          // group = (sub, half of the head dim): 4 k-steps
+                const int sub = grp >> 1, ks0 = (grp & 1) * 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) kf[0][i] = k_frag(kb, i);
+                for (int i = 0; i < 4; ++i)
+                    kf[buf][i] = *reinterpret_cast<const bf16x8_t *>(kb + sub * 32 * ROW_B + k_row_off +
+                                                                    (((2 * (ks0 + i) + lgrp) ^ k_sw) << 4));
+            };
+            read_k(0, 0);
 #pragma unroll
-        for (int grp = 0; grp < 4; ++grp) {
-            if (grp + 1 < 4) {
+            for (int grp = 0; grp < 4; ++grp) {
+                if (grp + 1 < 4) read_k((grp + 1) & 1, grp + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                const int sub = grp >> 1, ks0 = (grp & 1) * 4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) kf[(grp + 1) & 1][i] = k_frag(kb, 4 * (grp + 1) + i);
+                for (int i = 0; i < 4; ++i)
+                    s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[grp & 1][i], qf[ks0 + i], s[sub], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                s[grp >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[grp & 1][i], qf[(grp & 1) * 4 + i], s[grp >> 1], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
         }
-    };
-    // First half of the softmax step of a tile: mask (tiles touching the diagonal or the end of the cache only), row
-    // maximum, and -- only when some row of the wave saw a new maximum (wave-uniform branch; deep into a long cache
-    // the maxima have settled) -- the rescale of the running sum and output.  The scores stay unscaled: the softmax
-    // scale is positive, so the maximum is kept in raw units and the scale folded into the exponent.
-    auto mask_tile = [&](int t, f32x16_t (&s)[2]) {
-        const int j0 = (t_lo + t) * BN;
-        if ((j0 + BN - 1 > q_offset + m0 + wave * 32) || (j0 + BN > kv_len)) {
+        // --- mask (only tiles that touch the diagonal or the end of the cache).  The scores stay unscaled: the
+        //     softmax scale is positive, so the running maximum can be kept in raw units and the scale folded
+        //     into the exponent's multiply-add.
+        if (TAIL && ((j0 + BN - 1 > q_offset + m0 + wave * 32) || (j0 + BN > kv_len))) {
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -217,17 +228,26 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
                     if (key > q_abs || key >= kv_len) s[sub][r] = -INFINITY;
                 }
         }
-    };
-    auto row_max = [&](const f32x16_t (&s)[2]) {
         float mx = -INFINITY;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
-        return half_swap_max(mx);
-    };
-    auto apply_max = [&](float mx) {
+        mx = half_swap_max(mx);
         const float m_new = fmaxf(m_run, mx);
+        const float neg_m = -m_new * sc;
+        float psum = 0.f;
+        bf16x8_t pb[2][2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][r], sc, neg_m));
+                psum += p;
+                pb[sub][r / 8][r % 8] = (bf16_t)p;
+            }
+        // rescale the running sums only when some row of this wave saw a new maximum (wave-uniform branch):
+        // deep into a long cache the maxima have settled and the 64 multiplies per tile are skipped
         if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
             const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
             m_run = m_new;
@@ -237,149 +257,41 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
         }
-    };
-    // Second half: probabilities (bf16, already in the B-operand layout of the second product) and their sum.
-    auto probs = [&](const f32x16_t (&s)[2], bf16x8_t (&pb)[2][2]) {
-        const float neg_m = -m_run * sc;
-        float psum = 0.f;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][r], sc, neg_m));
-                psum += p;
-                pb[sub][r / 8][r % 8] = (bf16_t)p;
-            }
         l_run += psum;
-        asm volatile("" : "+v"(l_run));     // the sum is complete here (keeps the 32 probabilities from staying live)
-    };
-    // O^T += V^T P^T of tile t.  k-slots 8*lgrp .. +8 of MFMA step (sub, tt) hold keys 32 sub + 16 tt + 4 lgrp + {0..3}
-    // and 32 sub + 16 tt + 8 + 4 lgrp + {0..3}: two transposing reads.  The V fragments of one 32-dim block (4 MFMAs)
-    // are fetched while the previous block is multiplied.
-    // With s_max != NULL (interleaved body) the row maximum of that (next) tile's scores is computed between the MFMAs,
-    // eight values per 32-dim block, and returned, and the eight global -> LDS requests for K(t+2) and V(t+1) are
-    // issued two per block: in a burst at the top of the iteration they held the wave for several hundred cycles, and
-    // they cannot sit among the K fragment reads of the first product (LDS writes against LDS reads keep their order).
-    // V(t+1) always exists there; K(t+2) may lie past this group's tiles (last interleaved iteration): that request
-    // is harmless (rows past the cache read as zero, the stage is free and its content never used).
-    auto pv = [&](int t, const bf16x8_t (&pb)[2][2], const f32x16_t (*s_max)[2]) {
-        float mx = -INFINITY;
-        bf16x8_t vf[2][4];
-        const uint32_t vb_addr = lds_addr + (uint32_t)((t & 1) * STAGE_B + TILE_B + v_row_base * ROW_B + v_byte);
-        auto read_v = [&](int buf, int dt) {
-            const uint32_t a = vb_addr + (uint32_t)(((4 * dt + v_chunk_base) ^ v_sw) << 4);
-            vf[buf][0] = __builtin_shufflevector(lds_read_tr16<0 * ROW_B>(a), lds_read_tr16<8 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
-            vf[buf][1] = __builtin_shufflevector(lds_read_tr16<16 * ROW_B>(a), lds_read_tr16<24 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
-            vf[buf][2] = __builtin_shufflevector(lds_read_tr16<32 * ROW_B>(a), lds_read_tr16<40 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
-            vf[buf][3] = __builtin_shufflevector(lds_read_tr16<48 * ROW_B>(a), lds_read_tr16<56 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
-        };
-        read_v(0, 0);
-#pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) {
-            if (dt + 1 < D / 32) {
-                read_v((dt + 1) & 1, dt + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                lds_tr_wait<8>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);   // 8 younger reads may pend
-            } else {
-                __builtin_amdgcn_sched_barrier(0);
-                lds_tr_wait<0>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);
-            }
-#pragma unroll
-            for (int st = 0; st < 4; ++st)
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt & 1][st], pb[st >> 1][st & 1], o[dt], 0, 0, 0);
-            if (s_max) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) mx = fmaxf(mx, (*s_max)[dt >> 1][(dt & 1) * 8 + r]);
-                issue_one(t, 2 * dt);
-                issue_one(t, 2 * dt + 1);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        return s_max ? half_swap_max(mx) : mx;
-    };
-
-    // ---- the tile loop, software-pipelined by one tile: iteration t multiplies K(t+1) Q^T while it turns the scores
-    //      of tile t into probabilities, then adds V(t)^T P(t)^T.  The matrix instructions of the first product and the
-    //      exponentials of the previous tile are independent, so they are slotted between each other (one MFMA, one K
-    //      fragment read, eight vector instructions) and the wave keeps the matrix pipe fed through its own softmax
-    //      instead of relying on the other wave of the SIMD being in a different phase.  LDS: at the barrier of iteration
-    //      t the loads of K(t+1) and V(t) have landed; K(t+2) then overwrites K(t) (multiplied in iteration t-1) and
-    //      V(t+1) overwrites V(t-1).
-    // Tiles that lie entirely at or below the diagonal of the block's first row and inside the cache need no mask:
-    // they take the interleaved body.  The few tiles that touch the diagonal or the end of the cache, the last tile
-    // (nothing to multiply ahead) and the idle iterations of the shorter key group take the plain body.
-    static_assert(NSTAGE == 2, "two LDS stages");
-    const int n_plain_all = min((q_offset + m0 + 1) / BN, kv_len / BN);
-    const int n_pipe = max(0, min(min(n_plain_all - t_lo, n_tiles), n_tiles - 1));
-    f32x16_t sA[2], sB[2];
-    float mx_cur = 0.f;                     // row maximum of the current scores (interleaved body only)
-
-    if (n_tiles > 0) issue_k(0);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (n_tiles > 1) issue_k(1);
-    if (n_tiles > 0) {
-        issue_v(0);
-        qk_plain(0, sA);
-        mx_cur = row_max(sA);
-    }
-    auto top = [&]() {
-        __builtin_amdgcn_s_waitcnt(0);      // this wave's loads of K(t+1) and V(t) have landed
-        __syncthreads();                    // ... everyone's have, and K(t), V(t-1) are no longer being read
-    };
-    auto body_pipe = [&](int t, f32x16_t (&s_cur)[2], f32x16_t (&s_nxt)[2]) {
-        top();
-        apply_max(mx_cur);
-        bf16x8_t pb[2][2];
+        // --- O^T += V^T P^T.  k-slots 8*lgrp .. +8 of MFMA step (sub, t) hold keys
+        //     32 sub + 16 t + 4 lgrp + {0..3} and 32 sub + 16 t + 8 + 4 lgrp + {0..3}: two transposing reads.
+        //     The V fragments of one 32-dim block (4 MFMAs) are fetched while the previous block is multiplied.
         {
-            const unsigned char *kb = lds_g + ((t + 1) & 1) * STAGE_B;
-            bf16x8_t kf[16];
+            bf16x8_t vf[2][4];
+            const uint32_t vb_addr = lds_addr + (uint32_t)((jt % NSTAGE) * STAGE_B + TILE_B + v_row_base * ROW_B + v_byte);
+            auto read_v = [&](int buf, int dt) {
+                const uint32_t a = vb_addr + (uint32_t)(((4 * dt + v_chunk_base) ^ v_sw) << 4);
+                // MFMA step st = (sub, t) takes key rows 32 sub + 16 t + {0, 8} (+ the lane's row inside the block)
+                vf[buf][0] = __builtin_shufflevector(lds_read_tr16<0 * ROW_B>(a), lds_read_tr16<8 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+                vf[buf][1] = __builtin_shufflevector(lds_read_tr16<16 * ROW_B>(a), lds_read_tr16<24 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+                vf[buf][2] = __builtin_shufflevector(lds_read_tr16<32 * ROW_B>(a), lds_read_tr16<40 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+                vf[buf][3] = __builtin_shufflevector(lds_read_tr16<48 * ROW_B>(a), lds_read_tr16<56 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+            };
+            read_v(0, 0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kf[i] = k_frag(kb, i);
-            __builtin_amdgcn_sched_barrier(0);
-            const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int dt = 0; dt < D / 32; ++dt) {
+                if (dt + 1 < D / 32) {
+                    read_v((dt + 1) & 1, dt + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    lds_tr_wait<8>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);   // 8 younger reads may pend
+                } else {
+                    __builtin_amdgcn_sched_barrier(0);
+                    lds_tr_wait<0>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);
+                }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (i + 4 < 16) kf[i + 4] = k_frag(kb, i + 4);
-                s_nxt[i >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[i & 7], (i & 7) ? s_nxt[i >> 3] : zero, 0, 0, 0);
+                for (int st = 0; st < 4; ++st)
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt & 1][st], pb[st >> 1][st & 1], o[dt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            probs(s_cur, pb);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one K fragment read (four MFMAs ahead)
-                __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);   // nine of the ~130 vector instructions
-            }
-            __builtin_amdgcn_sched_barrier(0);
         }
-        mx_cur = pv(t, pb, &s_nxt);
     };
-    auto body_plain = [&](int t, f32x16_t (&s_cur)[2], f32x16_t (&s_nxt)[2]) {
-        top();
-        if (t + 2 < n_tiles) issue_k(t + 2);
-        if (t + 1 < n_tiles) issue_v(t + 1);
-        if (t >= n_tiles) return;           // the shorter key group idles through the remaining barriers
-        mask_tile(t, s_cur);
-        apply_max(row_max(s_cur));
-        if (t + 1 < n_tiles) qk_plain(t + 1, s_nxt);
-        bf16x8_t pb[2][2];
-        probs(s_cur, pb);
-        pv(t, pb, nullptr);
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) s_cur[sub] = s_nxt[sub];
-    };
-    int jt = 0;
-    for (; jt + 1 < n_pipe; jt += 2) {
-        body_pipe(jt, sA, sB);
-        body_pipe(jt + 1, sB, sA);
-    }
-    if (jt < n_pipe) {
-        body_pipe(jt, sA, sB);
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) sA[sub] = sB[sub];
-        ++jt;
-    }
-    for (; jt < n_iter; ++jt) body_plain(jt, sA, sB);
+    for (int jt = 0; jt < n_main; ++jt) tile(jt, std::false_type{});
+    for (int jt = n_main; jt < n_iter; ++jt) tile(jt, std::true_type{});
 
     if (KVS > 1) {
         // merge the two groups: group 1 parks (m, l, o) of its rows in LDS, group 0 folds them into its own.
@@ -397,21 +309,22 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
             xm[256 + t4] = l_run;
         }
         __syncthreads();
-        if (kgrp == 1) return;
-        const float m_b = xm[t4], l_b = xm[256 + t4];
-        const float m_new = fmaxf(m_run, m_b);
-        const float fa = __builtin_amdgcn_exp2f((m_run - m_new) * sc), fb = __builtin_amdgcn_exp2f((m_b - m_new) * sc);
-        l_run = l_run * fa + l_b * fb;
+        if (kgrp == 0) {
+            const float m_b = xm[t4], l_b = xm[256 + t4];
+            const float m_new = fmaxf(m_run, m_b);
+            const float fa = __builtin_amdgcn_exp2f((m_run - m_new) * sc), fb = __builtin_amdgcn_exp2f((m_b - m_new) * sc);
+            l_run = l_run * fa + l_b * fb;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
+            for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] = o[dt][r] * fa + xo[(dt * 16 + r) * 256 + t4] * fb;
+                for (int r = 0; r < 16; ++r) o[dt][r] = o[dt][r] * fa + xo[(dt * 16 + r) * 256 + t4] * fb;
+        }
     }
     // --- normalise and store: lane holds column q = lcol, rows d = 32 dt + 8 (r/4) + 4 lgrp + r%4
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_tot;
     const int row = m0 + wave * 32 + lcol;
-    if (row < Tc) {
+    if (kgrp == 0 && row < Tc) {
         bf16_t *op = Out + ((size_t)row * nq + h) * D;
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
@@ -422,6 +335,7 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
                 *reinterpret_cast<bf16x4_t *>(op + dt * 32 + 8 * r4 + 4 * lgrp) = v;
             }
     }
+    }   // row blocks of this workgroup
 #endif
 }
 
@@ -432,8 +346,10 @@ bool iso_attn_bf16_dtl_supported(int d, int kv_len, int nkv) {
     return d == D && (long long)kv_len * nkv * D * 2 < (1ll << 31);
 }
 
+// shape: 0 = chosen from the size; forced by tests and measurement: 1 = key split inside the workgroup, 2 = key split
+// and two row blocks per workgroup, 3 = one row block, two workgroups per compute unit.
 hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v, void *out, int Tc, int q_offset,
-                                    int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s) {
+                                    int kv_len, int nq, int nkv, int d, int q_stride, int shape, hipStream_t s) {
     if (d != D) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
@@ -445,15 +361,34 @@ hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v,
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((Tc + BM - 1) / BM, nq);
-    const long long wgs = (long long)grid.x * grid.y;
+    const int n_blocks = (Tc + BM - 1) / BM;
+    const long long wgs = (long long)n_blocks * nq;
     // Launches that cannot put two workgroups on every compute unit split the keys inside the workgroup (measured:
-    // 1.2-1.4x at 100-500 workgroups); larger ones run two independent workgroups per unit (3-8 % better there).
-    if (wgs < 512)
-        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2>), grid, dim3(512), 2 * 2 * STAGE_B, s, (const bf16_t *)q,
-                           (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride);
+    // 1.2-1.4x at 100-500 workgroups).  From about one workgroup per unit up to a few times what the chip holds at
+    // once, the workgroups also take two row blocks each (longest with shortest), so that all of them carry the same
+    // work -- provided the halved count fills its last round of the chip to 90 % (measured 1.05-1.36x; a three-quarter
+    // full third round loses instead).  Larger launches balance by themselves (longest row blocks first) and run two
+    // independent workgroups per unit (3-8 % better there).
+    static int ncu = 0;
+    if (ncu == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        ncu = n;
+    }
+    const long long paired = (long long)((n_blocks + 1) / 2) * nq;
+    const long long rounds = (paired + ncu - 1) / ncu;
+    const bool pair_ok = wgs >= 320 && wgs < 4096 && (paired <= ncu || paired * 10 >= 9 * rounds * ncu);
+    const int mode = shape >= 1 && shape <= 3 ? shape - 1 : (pair_ok ? 1 : wgs < 512 ? 0 : 2);
+    if (mode == 0)
+        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2>), dim3(n_blocks, nq), dim3(512), 2 * 2 * STAGE_B, s, (const bf16_t *)q,
+                           (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride, 0);
+    else if (mode == 1)
+        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2>), dim3((n_blocks + 1) / 2, nq), dim3(512), 2 * 2 * STAGE_B, s,
+                           (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq,
+                           nkv, q_stride, 1);
     else
-        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 1>), grid, dim3(256), 2 * STAGE_B, s, (const bf16_t *)q,
-                           (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride);
+        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 1>), dim3(n_blocks, nq), dim3(256), 2 * STAGE_B, s, (const bf16_t *)q,
+                           (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride, 0);
     return hipGetLastError();
 }

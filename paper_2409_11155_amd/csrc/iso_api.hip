@@ -190,7 +190,8 @@ int attention(iso_ctx *ctx, const void *q, int q_stride, const void *kc, const v
     hipError_t e;
     const bool mfma = c.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_ATTN);
     if (mfma && !(ctx->flags & ISO_FLAG_ATTN_STAGED) && iso_attn_bf16_dtl_supported(c.head_dim, kv_len, c.n_kv_heads))
-        e = iso_launch_attn_bf16_dtl(q, kc, vc, out, Tc, q_offset, kv_len, c.n_q_heads, c.n_kv_heads, c.head_dim, q_stride, s);
+        e = iso_launch_attn_bf16_dtl(q, kc, vc, out, Tc, q_offset, kv_len, c.n_q_heads, c.n_kv_heads, c.head_dim, q_stride,
+                                     (ctx->flags >> 12) & 3, s);
     else if (mfma && iso_attn_bf16_mfma_supported(c.head_dim))
         e = iso_launch_attn_bf16_mfma(q, kc, vc, out, Tc, q_offset, kv_len, c.n_q_heads, c.n_kv_heads, c.head_dim, q_stride, s);
     else

@@ -95,7 +95,7 @@ hipError_t iso_launch_attn_bf16_mfma(const void *q, const void *k, const void *v
                                      int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
 bool iso_attn_bf16_mfma_supported(int d);
 hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v, void *out, int Tc, int q_offset,
-                                    int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
+                                    int kv_len, int nq, int nkv, int d, int q_stride, int shape, hipStream_t s);
 bool iso_attn_bf16_dtl_supported(int d, int kv_len, int nkv);
 
 // ---- small device helpers ----------------------------------------------------------------------

@@ -184,7 +184,9 @@ ATTN_CASES = [
 
 @pytest.mark.parametrize("dt,d,flags", [("f32", 64, 0), ("f32", 128, 0), ("bf16", 128, 0),
                                         ("bf16", 128, iso.ISO_FLAG_ATTN_STAGED),
-                                        ("bf16", 128, iso.ISO_FLAG_SIMPLE_ATTN), ("bf16", 64, 0)])
+                                        ("bf16", 128, iso.ISO_FLAG_SIMPLE_ATTN), ("bf16", 64, 0),
+                                        # the three launch shapes of the direct-to-LDS kernel, forced (bits 12..13)
+                                        ("bf16", 128, 1 << 12), ("bf16", 128, 2 << 12), ("bf16", 128, 3 << 12)])
 @pytest.mark.parametrize("Tc,q_offset,kv_len,nq,nkv", ATTN_CASES)
 def test_attn_chunk(dt, d, flags, Tc, q_offset, kv_len, nq, nkv):
     q, k, v = iso_inputs.make_qkv_cache(Tc, kv_len, nq, nkv, d, seed=Tc + q_offset, dtype=dt)
@@ -200,6 +202,23 @@ def test_attn_chunk(dt, d, flags, Tc, q_offset, kv_len, nq, nkv):
             # |d out| <= 2^-9 * sum_j p_j |v_j| <= 2^-9 max|v|, on top of the 2^-8 output rounding
             rms = float(np.sqrt(np.mean(ref * ref)))
             tol = 2.0 ** -9 * float(np.abs(h64(v, dt)).max()) / rms + 2.0 ** -8 + 1e-4
+        err = orc.max_rel_err(f64(out), ref)
+        assert err <= tol, (err, tol)
+
+
+@pytest.mark.parametrize("Tc,q_offset,nq,nkv", [(2048, 1024, 32, 4), (1920, 0, 34, 2)])
+def test_attn_chunk_mid_size_launch_takes_two_row_blocks_per_workgroup(Tc, q_offset, nq, nkv):
+    """512 and more workgroups' worth of row blocks: the launch pairs the longest row block with the shortest
+    (chosen by itself here, not forced); an odd block count leaves the middle one alone."""
+    dt, d, kv_len = "bf16", 128, q_offset + Tc
+    q, k, v = iso_inputs.make_qkv_cache(Tc, kv_len, nq, nkv, d, seed=9, dtype=dt)
+    with make_ctx(256, nq, nkv, d, 64, dt, kv_len) as ctx:
+        out = iso.DeviceArray((Tc, nq * d), dt, fill_byte=NAN_BYTE)
+        ctx.attn_chunk(dev(q, dt), dev(k, dt), dev(v, dt), out, Tc, q_offset, kv_len, ctx.stream0)
+        ctx.sync()
+        ref = orc.attention_chunk(h64(q, dt), h64(k, dt), h64(v, dt), q_offset, kv_len).reshape(Tc, nq * d)
+        rms = float(np.sqrt(np.mean(ref * ref)))
+        tol = 2.0 ** -9 * float(np.abs(h64(v, dt)).max()) / rms + 2.0 ** -8 + 1e-4
         err = orc.max_rel_err(f64(out), ref)
         assert err <= tol, (err, tol)
 
