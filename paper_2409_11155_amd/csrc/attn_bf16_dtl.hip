@@ -133,6 +133,16 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
                 v_off[i] + tile_off, 0, 0, 0);
     };
 
+    auto issue_half = [&](int stage, int j0, int which) {    // which = 0: the K tile, 1: the V tile
+        unsigned char *base = lds_g + stage * STAGE_B + which * TILE_B;
+        const uint32_t tile_off = (uint32_t)j0 * row_stride;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                which ? rs_v : rs_k, (__attribute__((address_space(3))) void *)(base + (wave + 4 * i) * 1024), 16,
+                (which ? v_off[i] : k_off[i]) + tile_off, 0, 0, 0);
+    };
+
     // ---- LDS read addressing
     // K (A operand of S^T): lane = key row lcol of the 32-key block, 16-byte chunk 2*ks + lgrp, swizzled by row & 15
     const int k_row_off = lcol * ROW_B;
@@ -180,7 +190,9 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
         else
             __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();                    // ... everyone's have, and tile jt-1 is no longer being read
-        if (jt + NSTAGE - 1 < n_tiles) issue((jt + NSTAGE - 1) % NSTAGE, j0 + (NSTAGE - 1) * BN);
+        // Requests for the next tile.  In the branch-free body they are issued between the MFMAs of the first product
+        // (below); issued in one burst here they hold the wave for some 500 cycles.
+        if (TAIL && jt + NSTAGE - 1 < n_tiles) issue((jt + NSTAGE - 1) % NSTAGE, j0 + (NSTAGE - 1) * BN);
         if (TAIL) {
             if (KVS > 1 && jt >= n_tiles) return;   // the shorter group idles through the last barrier
             if (j0 > wave_q_max) return;            // every key of this tile is above this wave's diagonal
@@ -213,6 +225,18 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[grp & 1][i], qf[ks0 + i], s[sub], 0, 0, 0);
+                if (!TAIL && grp >= 2) {
+                    // Once the last K fragment reads are out (LDS writes keep their order against LDS reads), the
+                    // eight requests for tile jt+1 go one behind each remaining MFMA: K with the third group, V with
+                    // the fourth.  No test for the end of the range: a tile past this group's share is never used, its
+                    // stage is free, and rows past the cache read as zero.
+                    issue_half((jt + 1) % NSTAGE, j0 + BN, grp - 2);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
