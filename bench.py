@@ -43,6 +43,11 @@ def parse_args():
     return ap.parse_args()
 
 
+def note(msg: str) -> None:
+    """Progress on stderr (stdout carries the one JSON line): long workloads stay visibly alive."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def main() -> int:
     args = parse_args()
     if args.gpus != 1:
@@ -61,7 +66,9 @@ def main() -> int:
     dt = wl.dtype
     split = wl.split if args.split < 0 else args.split
     L = args.layers if args.layers > 0 else wl.n_layers
+    note(f"workload {args.workload}: T={T} layers={L} steps={args.steps} warmup={args.warmup}; drawing inputs")
     x_cpu, w_cpu = iso_inputs.make_workload_inputs(wl, seed=0)
+    note("uploading weights")
     if L == 1:
         layers = [iso.upload_weights(w_cpu, dt)]
     else:   # every layer owns its device buffers; the host draws only a few distinct sets (see --distinct-layers)
@@ -86,6 +93,7 @@ def main() -> int:
 
     def timed(sp, comm, sched):
         """W warm-up steps, then exactly K steps between two full synchronisations; ms per step."""
+        note(f"timing split={sp} comm={comm} sched={sched}")
         x.copy_from(x0)
         run(W, sp, comm, sched)
         ctx.sync()
@@ -158,6 +166,7 @@ def main() -> int:
     # Section 6: finer cuts than two chunks.  Cost-balanced cut points from the library's planner; chunks on the two
     # streams in turn, or one stream per chunk with the attention blocks chained in chunk order.
     def timed_chunks(bounds, comm, sched):
+        note(f"timing {len(bounds) + 1} chunks comm={comm} sched={sched}")
         def go(n):
             for _ in range(n):
                 ctx.stack_prefill_chunks(layers, x, kc, vc, T, bounds, comm, sched)
@@ -347,6 +356,7 @@ def main() -> int:
     # ---- the oracle on the host cores, bounded ---------------------------------------------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
+        note("timing the CPU oracle on a bounded sample")
         cpu_baseline = time_oracle(wl, x_cpu, w_cpu, split)
 
     layer_flops = wl.gemm_flops() * L + attn_flops

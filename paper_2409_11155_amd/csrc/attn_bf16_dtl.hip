@@ -388,8 +388,8 @@ hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v,
     const int n_blocks = (Tc + BM - 1) / BM;
     const long long wgs = (long long)n_blocks * nq;
     // Launches that cannot put two workgroups on every compute unit split the keys inside the workgroup (measured:
-    // 1.2-1.4x at 100-500 workgroups).  From about one workgroup per unit up to a few times what the chip holds at
-    // once, the workgroups also take two row blocks each (longest with shortest), so that all of them carry the same
+    // 1.2-1.4x at 100-500 workgroups).  From about one workgroup per unit up to four times what the chip holds at
+    // once (beyond that, deep in a long cache, plain launches measured 4 % better), the workgroups also take two row blocks each (longest with shortest), so that all of them carry the same
     // work -- provided the halved count fills its last round of the chip to 90 % (measured 1.05-1.36x; a three-quarter
     // full third round loses instead).  Larger launches balance by themselves (longest row blocks first) and run two
     // independent workgroups per unit (3-8 % better there).
@@ -402,7 +402,7 @@ hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v,
     }
     const long long paired = (long long)((n_blocks + 1) / 2) * nq;
     const long long rounds = (paired + ncu - 1) / ncu;
-    const bool pair_ok = wgs >= 320 && wgs < 4096 && (paired <= ncu || paired * 10 >= 9 * rounds * ncu);
+    const bool pair_ok = wgs >= 320 && wgs <= 2048 && (paired <= ncu || paired * 10 >= 9 * rounds * ncu);
     const int mode = shape >= 1 && shape <= 3 ? shape - 1 : (pair_ok ? 1 : wgs < 512 ? 0 : 2);
     if (mode == 0)
         hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2>), dim3(n_blocks, nq), dim3(512), 2 * 2 * STAGE_B, s, (const bf16_t *)q,
