@@ -180,6 +180,7 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
     // the cache (and the idle iterations of the shorter key group) take the general body.
     const int n_plain_all = min((q_offset + m0 + 1) / BN, kv_len / BN);
     const int n_main = max(0, min(n_plain_all - t_lo, n_tiles));
+    static_assert(NSTAGE == 2, "the branch-free body requests tile jt+1 while tile jt is multiplied: two stages");
     auto tile = [&](int jt, auto tail_c) {
         constexpr bool TAIL = decltype(tail_c)::value;
         const int j0 = (t_lo + jt) * BN;

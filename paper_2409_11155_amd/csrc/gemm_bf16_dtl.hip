@@ -402,25 +402,30 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                     }
                 }
                 __syncthreads();
+                // Sixteen 16-byte loads in flight at a time, then their adds: left to itself the compiler waits for
+                // every load before the next one, and a cache-bypassing load is a trip to memory (8 us per partial
+                // tile that way, measured).
+                constexpr int NV = TM * TN * 4, BATCH = 16;
+                static_assert(NV % BATCH == 0, "partial tile is a whole number of load batches");
                 for (int j = qfirst; j < q; ++j) {
-                    const int src = wg_of(j);
+                    const uint32_t src_off = (uint32_t)(wg_of(j) * (int)Cfg::SLOT_BYTES) + (uint32_t)tid * 16u;
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+                    for (int b0 = 0; b0 < NV; b0 += BATCH) {
+                        f32x4_t t[BATCH];
 #pragma unroll
-                        for (int jj = 0; jj < TN; ++jj)
+                        for (int k = 0; k < BATCH; ++k)
+                            t[k] = __builtin_bit_cast(
+                                f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                             rs_p, src_off + (uint32_t)((b0 + k) * Cfg::NT * 16), 0, SK_COHERENT));
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                            for (int v4 = 0; v4 < 4; ++v4) {
-                                const f32x4_t v = __builtin_bit_cast(
-                                    f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                                 rs_p,
-                                                 (uint32_t)(src * (int)Cfg::SLOT_BYTES +
-                                                            (((i * TN + jj) * 4 + v4) * Cfg::NT + tid) * 16),
-                                                 0, SK_COHERENT));
-                                acc[i][jj][4 * v4] += v[0];
-                                acc[i][jj][4 * v4 + 1] += v[1];
-                                acc[i][jj][4 * v4 + 2] += v[2];
-                                acc[i][jj][4 * v4 + 3] += v[3];
-                            }
+                        for (int k = 0; k < BATCH; ++k) {
+                            const int e = b0 + k, ij = e / 4, v4 = e % 4;
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) acc[ij / TN][ij % TN][4 * v4 + c] += t[k][c];
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
             store_tile();
@@ -510,13 +515,15 @@ static int pick_variant(int M, int N) {
     return tiles_256 >= 128 ? 1 : 3;
 }
 
-// Stream-K or one tile per workgroup?  Measured over the same shapes: with at least ~40 k-slices per team the
-// stream-K launch wins (every compute unit busy whatever the tile count, and team members share their W slices in
-// L2); with less k depth the cost of parking and fetching the partial tiles (about 13 us per workgroup) dominates.
+// Stream-K or one tile per workgroup?  Measured over the same shapes: with at least ~20 k-slices per team the
+// stream-K launch wins or ties (every compute unit busy whatever the tile count, and team members share their W slices
+// in L2: 1024x4992x6656 at 32 slices per team +13 %, 2048x1280x8192 at 20 +29 %, 2048x8192x1024 at 16 even); with less
+// k depth the cost of parking and fetching the partial tiles (about 6 us per workgroup) dominates (1024x6656x1664 at
+// 11 slices per team: 52 against 37 us).
 static bool sk_wanted(int M, int N, int K, const iso_sk_ws *sk) {
     if (!sk || !sk->base || sk->num_wg < 8) return false;
     int TS, G, grouped;
-    return sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped) >= 40 && grouped;
+    return sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped) >= 20 && grouped;
 }
 
 // What a launch with variant 0 would do on a device with num_wg compute units (host only, no device call).

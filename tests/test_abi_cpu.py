@@ -118,7 +118,8 @@ def test_gemm_launch_plan_choices_and_invariants():
     # the projections of the 30B TP=4 chunk (M = 1024) and of the 70B TP=4 chunk (M = 4096) on 256 compute units
     assert iso.gemm_launch_plan(1024, 8960, 6656) == (SK, 4, 256)          # gate/up: 35 columns x 104 slices / 64 teams
     assert iso.gemm_launch_plan(1024, 6656, 1664)[0] == T128               # o_proj: only 10 slices per team
-    assert iso.gemm_launch_plan(1024, 6656, 4480)[0] == T128               # down: 28 slices per team
+    assert iso.gemm_launch_plan(1024, 6656, 4480) == (SK, 4, 256)          # down: 28 slices per team
+    assert iso.gemm_launch_plan(2048, 8192, 1024)[0] == T256               # 70B TP=8 o_proj: 16 slices per team
     assert iso.gemm_launch_plan(4096, 8192, 7168) == (SK, 8, 256)
     assert iso.gemm_launch_plan(4096, 8192, 7168, num_cu=0) == (T256, 1, 512)   # no workspace: one tile per workgroup
     assert iso.gemm_launch_plan(300, 257 * 8, 1000)[0] in (iso.ISO_GEMM_STAGED, iso.ISO_GEMM_SIMPLE)   # K % 64 != 0
@@ -134,7 +135,7 @@ def test_gemm_launch_plan_choices_and_invariants():
             assert team in (1, 2, 4, 8) and tiles_m % team == 0
             assert 0 < grid <= cus and grid % (8 * team) == 0
             teams = grid // team
-            assert (tiles_m // team) * tiles_n * nk // teams >= 40
+            assert (tiles_m // team) * tiles_n * nk // teams >= 20
         elif kind == T256:
             assert grid == tiles_m * tiles_n and grid >= 128
         else:
