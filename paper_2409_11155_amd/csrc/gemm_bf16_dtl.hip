@@ -41,6 +41,11 @@ template <int BM, int BN, int WM, int WN> struct DtlCfg {
     static constexpr int CP = WTN + 8;                                          // epilogue LDS row pitch (elements)
     static constexpr int EPI_BYTES = NWAVES * WTM * CP * 2;
     static constexpr int LDS_BYTES = (2 * STAGE > EPI_BYTES) ? 2 * STAGE : EPI_BYTES;
+    // Interleaved main loop of the 256x256 tile: a third LDS stage for the W tile only (the whole 160 KB of a compute
+    // unit).  W slices are then requested two slices ahead instead of one; weights come from HBM (a layer's weights
+    // pass through the memory-side cache once per step), the activations from cache, so only W needs the distance.
+    static constexpr bool W3 = BM == 256 && BN == 256 && NWAVES == 8;
+    static constexpr int LDS_BYTES_W3 = 2 * A_BYTES + 3 * W_BYTES;
     static constexpr size_t SLOT_BYTES = (size_t)BM * BN * 4;                   // one fp32 partial tile
     static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "wave-loads must divide evenly");
 };
@@ -114,18 +119,31 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
             w_off[i] = ((uint32_t)grow * (uint32_t)K + chunk * 8) * 2u;
         }
     };
-    auto issue = [&](int stage, int k0) {
-        unsigned char *base = lds + stage * STAGE;
+    // LDS layout.  Two stages of [A tile | W tile]; or, with three W stages, the two A tiles first and the three W
+    // tiles behind them.
+    constexpr bool W3 = PIPE && Cfg::W3;
+    constexpr int WS = W3 ? 3 : 2;
+    constexpr int A_STRIDE = W3 ? A_BYTES : STAGE, W_ORIGIN = W3 ? 2 * A_BYTES : A_BYTES;
+    constexpr int W_STRIDE = W3 ? Cfg::W_BYTES : STAGE;
+    auto issue_a = [&](int stage, int k0) {
+        unsigned char *base = lds + stage * A_STRIDE;
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rs_a, (__attribute__((address_space(3))) void *)(base + (wave + NWAVES * i) * 1024), 16, a_off[i],
                 k0 * 2, 0, 0);
+    };
+    auto issue_w = [&](int stage, int k0) {
+        unsigned char *base = lds + W_ORIGIN + stage * W_STRIDE;
 #pragma unroll
         for (int i = 0; i < W_LOADS; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_w, (__attribute__((address_space(3))) void *)(base + A_BYTES + (wave + NWAVES * i) * 1024), 16,
-                w_off[i], k0 * 2, 0, 0);
+                rs_w, (__attribute__((address_space(3))) void *)(base + (wave + NWAVES * i) * 1024), 16, w_off[i],
+                k0 * 2, 0, 0);
+    };
+    auto issue = [&](int stage, int k0) {
+        issue_a(stage, k0);
+        issue_w(stage, k0);
     };
 
     // ---- LDS side: byte offsets of this lane's operand rows; the k chunk is XOR-ed in per k-step
@@ -139,21 +157,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int r = wn * Cfg::WTN + j * 32 + lrow;
-        w_row_off[j] = A_BYTES + r * ROW_BYTES;
+        w_row_off[j] = W_ORIGIN + r * ROW_BYTES;
         w_sw[j] = swz(r);
     }
 
     f32x16_t acc[TM][TN];
     bf16x8_t af[2][TM], wf[2][TN];
-    auto read_frags = [&](const unsigned char *base, int buf, int ks) {
+    auto read_frags2 = [&](const unsigned char *abase, const unsigned char *wbase, int buf, int ks) {
         const int chunk = ks * 2 + lgrp;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            af[buf][i] = *reinterpret_cast<const bf16x8_t *>(base + a_row_off[i] + ((chunk ^ a_sw[i]) << 4));
+            af[buf][i] = *reinterpret_cast<const bf16x8_t *>(abase + a_row_off[i] + ((chunk ^ a_sw[i]) << 4));
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            wf[buf][j] = *reinterpret_cast<const bf16x8_t *>(base + w_row_off[j] + ((chunk ^ w_sw[j]) << 4));
+            wf[buf][j] = *reinterpret_cast<const bf16x8_t *>(wbase + w_row_off[j] + ((chunk ^ w_sw[j]) << 4));
     };
+    auto read_frags = [&](const unsigned char *base, int buf, int ks) { read_frags2(base, base, buf, ks); };
     auto mfma_step = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -177,6 +196,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
         __syncthreads();
         read_frags(lds, 0, 0);
         if (n > 1) issue(1, (kb + 1) * BK);
+        if (W3 && n > 1) issue_w(2, (kb + min(2, n - 1)) * BK);
         if (!PIPE) {
             for (int kt = 0; kt < n; ++kt) {
                 const unsigned char *base = lds + (kt & 1) * STAGE;
@@ -219,24 +239,40 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                     }
                 }
             };
+            // With three W stages the hand-over waits for everything but the W_LOADS youngest requests (vector-memory
+            // loads complete in order and a hand-over issues its A requests before its W requests, so what may still be
+            // out is the W tile two slices ahead); a request past the last slice re-reads the last slice into a free
+            // stage, which keeps that count the same to the end.
+            constexpr int WAIT_HANDOVER = W3 ? ((W_LOADS & 15) | (7 << 4)) : 0;
+            int wst = 0;                             // W stage of the current slice (kt % WS)
             auto slice = [&](int kt, auto handover, auto more) {
-                const unsigned char *base = lds + (kt & 1) * STAGE;
+                const int wnx = wst + 1 == WS ? 0 : wst + 1;
+                const unsigned char *abase = lds + (kt & 1) * A_STRIDE, *wbase = lds + wst * W_STRIDE;
 #pragma unroll
                 for (int ks = 0; ks < BK / 16 - 1; ++ks) {
-                    read_frags(base, (ks + 1) & 1, ks + 1);
+                    read_frags2(abase, wbase, (ks + 1) & 1, ks + 1);
                     mfma_step(ks & 1);
                     weave(false);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if (handover) {
-                    __builtin_amdgcn_s_waitcnt(0);   // next slice's loads landed; my last fragments are in registers
-                    __syncthreads();                 // ... for every wave: stage (kt & 1) is free, the other is full
-                    read_frags(lds + ((kt + 1) & 1) * STAGE, 0, 0);
-                    if (more) issue(kt & 1, (kb + kt + 2) * BK);
+                    __builtin_amdgcn_s_waitcnt(WAIT_HANDOVER);   // next slice's loads landed; my last fragments are in registers
+                    // ... for every wave: A stage (kt & 1) and W stage wst are free, the next slice is complete.  The
+                    // bare instruction: the barrier intrinsic brings a fence that waits for ALL outstanding loads; the
+                    // wait above is the fence this hand-over needs, and the memory clobber keeps LDS accesses in place.
+                    if (W3) asm volatile("s_barrier" ::: "memory");
+                    else __syncthreads();
+                    read_frags2(lds + ((kt + 1) & 1) * A_STRIDE, lds + wnx * W_STRIDE, 0, 0);
+                    if (more) {
+                        issue_a(kt & 1, (kb + kt + 2) * BK);
+                        if (W3) issue_w(wst, (kb + min(kt + 3, n - 1)) * BK);
+                        else issue_w(kt & 1, (kb + kt + 2) * BK);
+                    }
                 }
                 mfma_step((BK / 16 - 1) & 1);
                 if (handover) weave(more);
                 __builtin_amdgcn_sched_barrier(0);
+                wst = wnx;
             };
             for (int kt = 0; kt < n - 2; ++kt) slice(kt, std::true_type{}, std::true_type{});
             if (n >= 2) slice(n - 2, std::true_type{}, std::false_type{});
@@ -437,17 +473,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
 template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE>
 hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     using Cfg = DtlCfg<BM, BN, WM, WN>;
+    constexpr int LDS_BYTES = (PIPE && Cfg::W3) ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
     static bool attr_set = false;
     auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWIGLU, PIPE, false>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     dim3 grid(tiles_m * tiles_n), block(Cfg::NT);
-    hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
+    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
                        K, tiles_m, tiles_n, (unsigned char *)nullptr, 0u, (unsigned *)nullptr, 1, 0);
     return hipGetLastError();
 }
@@ -478,11 +515,12 @@ long long sk_plan(int M, int N, int K, int num_wg, int *TS_, int *G_, int *group
 template <bool SWIGLU>
 hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K, iso_sk_ws *sk, hipStream_t s) {
     using Cfg = DtlCfg<256, 256, 4, 2>;
+    constexpr int LDS_BYTES = Cfg::W3 ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
     static bool attr_set = false;
     auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, SWIGLU, true, true>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -491,7 +529,7 @@ hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K,
     sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped);
     ++sk->epoch;
     dim3 grid(G), block(Cfg::NT);
-    hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
+    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
                        K, tiles_m, tiles_n, (unsigned char *)sk->base, sk->epoch, sk->err, TS, grouped);
     return hipGetLastError();
 }
