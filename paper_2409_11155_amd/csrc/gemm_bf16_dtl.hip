@@ -8,7 +8,8 @@
 //     avoiding swizzle is applied on the GLOBAL side: lane (row r, slot p) fetches 16-byte chunk
 //     p ^ swz(r) of its row, so chunk c of row r lives in slot c ^ swz(r); the 16-byte operand reads of
 //     32 consecutive rows then spread over all 64 banks (measured: 0 bank conflicts).
-//   * Workgroup tile BM x BN (up to 256 x 256), k slice 64, two LDS stages; WM x WN wavefronts, each
+//   * Workgroup tile BM x BN (up to 256 x 256), k slice 64, two LDS stages (a third one for W where the LDS allows,
+//     so that weight slices are requested two slices ahead); WM x WN wavefronts, each
 //     owning a (BM/WM) x (BN/WN) block of 32x32x16 MFMA tiles.  The 8-wave shapes put two waves on every
 //     SIMD, which is what keeps the matrix pipe fed: a single wave cannot issue MFMAs back to back without
 //     gaps (a register-only MFMA loop reaches ~82 % of peak with one wave per SIMD, ~99 % with two).
@@ -41,11 +42,13 @@ template <int BM, int BN, int WM, int WN> struct DtlCfg {
     static constexpr int CP = WTN + 8;                                          // epilogue LDS row pitch (elements)
     static constexpr int EPI_BYTES = NWAVES * WTM * CP * 2;
     static constexpr int LDS_BYTES = (2 * STAGE > EPI_BYTES) ? 2 * STAGE : EPI_BYTES;
-    // Interleaved main loop of the 256x256 tile: a third LDS stage for the W tile only (the whole 160 KB of a compute
-    // unit).  W slices are then requested two slices ahead instead of one; weights come from HBM (a layer's weights
-    // pass through the memory-side cache once per step), the activations from cache, so only W needs the distance.
-    static constexpr bool W3 = BM == 256 && BN == 256 && NWAVES == 8;
+    // Interleaved main loop: a third LDS stage for the W tile only, wherever the 160 KB of a compute unit allow it
+    // (the 256x256 tile then takes all of it; the four-wave 128x128 tile, two workgroups per unit, 80 KB each).  W
+    // slices are then requested two slices ahead instead of one; weights come from HBM (a layer's weights pass through
+    // the memory-side cache once per step), the activations from cache, so only W needs the distance.
     static constexpr int LDS_BYTES_W3 = 2 * A_BYTES + 3 * W_BYTES;
+    static constexpr int WGS_PER_CU = (NWAVES == 4 && 2 * LDS_BYTES <= 160 * 1024) ? 2 : 1;
+    static constexpr bool W3 = LDS_BYTES_W3 * WGS_PER_CU <= 160 * 1024 && LDS_BYTES_W3 >= EPI_BYTES;
     static constexpr size_t SLOT_BYTES = (size_t)BM * BN * 4;                   // one fp32 partial tile
     static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "wave-loads must divide evenly");
 };
