@@ -34,7 +34,13 @@ template <int BM, int BN, int WM, int WN> struct F8Cfg {
     static constexpr int TM = WTM / 32, TN = WTN / 32;
     static constexpr int CP = WTN + 8;
     static constexpr int EPI_BYTES = NWAVES * WTM * CP * 2;
-    static constexpr int LDS_BYTES = (2 * STAGE > EPI_BYTES) ? 2 * STAGE : EPI_BYTES;
+    // two stages of [A tile | W tile], or -- where the 160 KB of a compute unit allow it -- two A tiles followed by
+    // three W tiles: weight slices are then requested two slices ahead (they come from HBM, the activations from cache)
+    static constexpr int LDS_BYTES_2 = (2 * STAGE > EPI_BYTES) ? 2 * STAGE : EPI_BYTES;
+    static constexpr int LDS_BYTES_W3 = 2 * A_BYTES + 3 * W_BYTES;
+    static constexpr int WGS_PER_CU = (NWAVES == 4 && 2 * LDS_BYTES_2 <= 160 * 1024) ? 2 : 1;
+    static constexpr bool W3 = LDS_BYTES_W3 * WGS_PER_CU <= 160 * 1024 && LDS_BYTES_W3 >= EPI_BYTES;
+    static constexpr int LDS_BYTES = W3 ? LDS_BYTES_W3 : LDS_BYTES_2;
     static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "wave-loads must divide evenly");
 };
 
@@ -101,18 +107,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_fp8_dtl_kernel(const unsign
         }
         w_off[i] = (uint32_t)grow * (uint32_t)K + chunk * 16;
     }
-    auto issue = [&](int stage, int kt) {
-        unsigned char *base = lds + stage * STAGE;
+    constexpr bool W3 = Cfg::W3;
+    constexpr int WS = W3 ? 3 : 2;
+    constexpr int A_STRIDE = W3 ? A_BYTES : STAGE, W_ORIGIN = W3 ? 2 * A_BYTES : A_BYTES;
+    constexpr int W_STRIDE = W3 ? Cfg::W_BYTES : STAGE;
+    auto issue_a = [&](int stage, int kt) {
+        unsigned char *base = lds + stage * A_STRIDE;
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rs_a, (__attribute__((address_space(3))) void *)(base + (wave + NWAVES * i) * 1024), 16, a_off[i],
                 kt * KE, 0, 0);
+    };
+    auto issue_w = [&](int stage, int kt) {
+        unsigned char *base = lds + W_ORIGIN + stage * W_STRIDE;
 #pragma unroll
         for (int i = 0; i < W_LOADS; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_w, (__attribute__((address_space(3))) void *)(base + A_BYTES + (wave + NWAVES * i) * 1024), 16,
-                w_off[i], kt * KE, 0, 0);
+                rs_w, (__attribute__((address_space(3))) void *)(base + (wave + NWAVES * i) * 1024), 16, w_off[i],
+                kt * KE, 0, 0);
     };
 
     // ---- LDS side
@@ -126,7 +139,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_fp8_dtl_kernel(const unsign
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int r = wn * Cfg::WTN + j * 32 + lrow;
-        w_row_off[j] = A_BYTES + r * ROW_BYTES;
+        w_row_off[j] = W_ORIGIN + r * ROW_BYTES;
         w_sw[j] = swz(r);
     }
 
@@ -146,11 +159,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_fp8_dtl_kernel(const unsign
         const i32x4_t hi = *reinterpret_cast<const i32x4_t *>(row + (((c0 + 1) ^ sw_) << 4));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    auto read_frags = [&](const unsigned char *base, int buf, int ks) {
+    auto read_frags = [&](const unsigned char *abase, const unsigned char *wbase, int buf, int ks) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[buf][i] = read_frag(base + a_row_off[i], a_sw[i], ks);
+        for (int i = 0; i < TM; ++i) af[buf][i] = read_frag(abase + a_row_off[i], a_sw[i], ks);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) wf[buf][j] = read_frag(base + w_row_off[j], w_sw[j], ks);
+        for (int j = 0; j < TN; ++j) wf[buf][j] = read_frag(wbase + w_row_off[j], w_sw[j], ks);
     };
     auto mfma_step = [&](int buf) {
 #pragma unroll
@@ -173,28 +186,46 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_fp8_dtl_kernel(const unsign
             }
         }
     };
+    // With three W stages the hand-over waits for everything but the W_LOADS youngest requests (vector-memory loads
+    // complete in order and a hand-over issues its A requests before its W requests, so what may still be out is the W
+    // tile two slices ahead); a request past the last slice re-reads the last slice into a free stage, which keeps
+    // that count the same to the end.
+    constexpr int WAIT_HANDOVER = W3 ? ((W_LOADS & 15) | (7 << 4)) : 0;
+    int wst = 0;                             // W stage of the current slice (kt % WS)
     auto slice = [&](int kt, auto handover, auto more) {
-        const unsigned char *base = lds + (kt & 1) * STAGE;
-        read_frags(base, 1, 1);              // second k-step of this slice
+        const int wnx = wst + 1 == WS ? 0 : wst + 1;
+        read_frags(lds + (kt & 1) * A_STRIDE, lds + wst * W_STRIDE, 1, 1);   // second k-step of this slice
         mfma_step(0);
         weave(false);
         __builtin_amdgcn_sched_barrier(0);
         if (handover) {
-            __builtin_amdgcn_s_waitcnt(0);   // next slice's loads landed; my last fragments are in registers
-            __syncthreads();                 // ... for every wave: stage (kt & 1) is free, the other is full
-            read_frags(lds + ((kt + 1) & 1) * STAGE, 0, 0);
-            if (more) issue(kt & 1, kt + 2);
+            __builtin_amdgcn_s_waitcnt(WAIT_HANDOVER);   // next slice's loads landed; my last fragments are in registers
+            // ... for every wave: A stage (kt & 1) and W stage wst are free, the next slice is complete.  The bare
+            // instruction where loads stay outstanding: the barrier intrinsic brings a fence that waits for all of them.
+            if (W3) asm volatile("s_barrier" ::: "memory");
+            else __syncthreads();
+            read_frags(lds + ((kt + 1) & 1) * A_STRIDE, lds + wnx * W_STRIDE, 0, 0);
+            if (more) {
+                issue_a(kt & 1, kt + 2);
+                issue_w(W3 ? wst : (kt & 1), W3 ? min(kt + 3, nk - 1) : kt + 2);
+            }
         }
         mfma_step(1);
         if (handover) weave(more);
         __builtin_amdgcn_sched_barrier(0);
+        wst = wnx;
     };
 
-    issue(0, 0);
+    issue_a(0, 0);
+    issue_w(0, 0);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    read_frags(lds, 0, 0);
-    if (nk > 1) issue(1, 1);
+    read_frags(lds, lds, 0, 0);
+    if (nk > 1) {
+        issue_a(1, 1);
+        issue_w(1, 1);
+        if (W3) issue_w(2, min(2, nk - 1));
+    }
     for (int kt = 0; kt < nk - 2; ++kt) slice(kt, std::true_type{}, std::true_type{});
     if (nk >= 2) slice(nk - 2, std::true_type{}, std::false_type{});
     slice(nk - 1, std::false_type{}, std::false_type{});
