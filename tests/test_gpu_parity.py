@@ -110,7 +110,9 @@ def test_swiglu(dt, T, F):
 # ------------------------------------------------------------------------------ projections
 
 GEMM_SHAPES = [(1, 8, 8), (64, 128, 64), (128, 128, 64), (129, 130, 72), (300, 257, 1000), (77, 768, 256),
-               (256, 384, 688), (513, 1280, 2048), (1000, 520, 1664), (260, 8, 64)]
+               (256, 384, 688), (513, 1280, 2048), (1000, 520, 1664), (260, 8, 64),
+               # two, three and five k-slices: the ends of the direct-to-LDS pipeline (three W stages, two A stages)
+               (200, 264, 128), (300, 520, 192), (70, 136, 320)]
 
 
 @pytest.mark.parametrize("dt,flags", [("f32", 0), ("bf16", 0), ("bf16", iso.ISO_FLAG_GEMM_STAGED),
