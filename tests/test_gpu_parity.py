@@ -303,6 +303,7 @@ def test_comm_stand_in_delivers_both_partials_to_the_host():
 @pytest.mark.parametrize("hidden,nq,nkv,ffn,T,splits", [
     (512, 4, 1, 768, 300, (0, 130, 299)),       # GQA, ragged everything
     (384, 3, 3, 200, 257, (128, 1)),            # MHA, odd head count
+    (128, 2, 1, 192, 260, (0, 100)),            # two and three k-slices in the projections
 ])
 def test_small_bf16_layer_all_rows(flags, hidden, nq, nkv, ffn, T, splits):
     d, dt = 128, "bf16"
