@@ -218,7 +218,8 @@ enum {
     ISO_FLAG_NO_STREAMK = 32, /* never pick the stream-K launch of the direct-to-LDS GEMM by itself  */
     ISO_FLAG_FP8_GEMM = 64    /* bf16 layers: run the four projections on the FP8 matrix cores (needs the FP8
                                  weights in iso_weights; activations are quantised per token row on the fly) */
-    /* bits 8..11: tile variant of the direct-to-LDS GEMM (0 = chosen from the shape) */
+    /* bits 8..11: tile variant of the direct-to-LDS GEMM (0 = chosen from the shape; 6 = its stream-K launch, which
+     * this value also forces for the FP8 GEMM) */
     /* bits 12..13: launch shape of the direct-to-LDS attention (0 = chosen from the size; 1 = key tiles split inside
      * the workgroup; 2 = that, and two row blocks (longest with shortest) per workgroup; 3 = one row block per
      * workgroup, two workgroups per compute unit) */

@@ -492,26 +492,9 @@ hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hi
     return hipGetLastError();
 }
 
-// Stream-K launch shape.  Team size: the largest power of two (at most 8) that tiles the tile rows without idle
-// members; the grouped mapping needs 8 * TS to divide the grid and every team a non-empty span, otherwise teams
-// of one in launch order.  Returns the k-slices each team gets.
+// Stream-K launch shape of this kernel (64-element k-slices): see iso_gemm_sk_plan below.
 long long sk_plan(int M, int N, int K, int num_wg, int *TS_, int *G_, int *grouped_) {
-    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256, nk = K / BK;
-    int TS = 1;
-    for (int t = 2; t <= 8; t *= 2)
-        if (tiles_m % t == 0) TS = t;
-    int G = (num_wg / (8 * TS)) * 8 * TS, grouped = 1;
-    long long units = (long long)(tiles_m / TS) * tiles_n * nk;
-    if (G < 8 * TS || units < G / TS) {   // tiny problem or odd device
-        TS = 1;
-        grouped = 0;
-        units = (long long)tiles_m * tiles_n * nk;
-        G = units < num_wg ? (int)units : num_wg;
-    }
-    *TS_ = TS;
-    *G_ = G;
-    *grouped_ = grouped;
-    return units / (G / TS);
+    return iso_gemm_sk_plan(M, N, K / BK, num_wg, TS_, G_, grouped_);
 }
 
 // stream-K launch of the 256x256 tile: one workgroup per compute unit
@@ -538,6 +521,30 @@ hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K,
 }
 
 }  // namespace
+
+// Stream-K launch shape for an M x N product of nk k-slices on num_wg compute units (shared by the bf16 and FP8
+// kernels).  Team size: the largest power of two (at most 8) that tiles the tile rows without idle members; the grouped
+// mapping needs 8 * TS to divide the grid and every team a non-empty span, otherwise teams of one in launch order.
+// Returns the k-slices each team gets.
+long long iso_gemm_sk_plan(int M, int N, int nk, int num_wg, int *TS_, int *G_, int *grouped_) {
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    int TS = 1;
+    for (int t = 2; t <= 8; t *= 2)
+        if (tiles_m % t == 0) TS = t;
+    int G = (num_wg / (8 * TS)) * 8 * TS, grouped = 1;
+    long long units = (long long)(tiles_m / TS) * tiles_n * nk;
+    if (G < 8 * TS || units < G / TS) {   // tiny problem or odd device
+        TS = 1;
+        grouped = 0;
+        units = (long long)tiles_m * tiles_n * nk;
+        G = units < num_wg ? (int)units : num_wg;
+    }
+    *TS_ = TS;
+    *G_ = G;
+    *grouped_ = grouped;
+    return units / (G / TS);
+}
+
 
 size_t iso_gemm_sk_ws_bytes(int num_wg) { return SK_HDR + (size_t)num_wg * DtlCfg<256, 256, 4, 2>::SLOT_BYTES; }
 int iso_gemm_sk_max_wg(void) { return SK_MAX_WG; }

@@ -160,7 +160,7 @@ int gemm(iso_ctx *ctx, int kind, const void *a, const void *w, void *c, int M, i
         Timed t_(ctx, kind, s);
         return for_segments(ctx, M, [&](int lo, int n) {
             hipError_t e = iso_launch_gemm_fp8(a8 + (size_t)lo * K, sa + lo, f8.w8, f8.sw, (char *)c + (size_t)lo * N * e_,
-                                               n, N, K, s);
+                                               n, N, K, (ctx->flags >> 8) & 15, sk_for(ctx, s), s);
             if (e != hipSuccess) return fail(ISO_ERR_HIP, "fp8 gemm launch (M=%d N=%d K=%d): %s", n, N, K, hipGetErrorString(e));
             return (int)ISO_OK;
         });
@@ -313,7 +313,7 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
         Timed t_(ctx, ISO_K_GEMM_GATE_UP, ck.s);
         ISO_TRY(for_segments(ctx, ck.n, [&](int lo, int n) {
             hipError_t e_ = iso_launch_gemm_swiglu_fp8(a8 + (size_t)lo * H, sa + lo, f8gu.w8, f8gu.sw, actr + (size_t)lo * F * e,
-                                                       n, F, H, ck.s);
+                                                       n, F, H, (ctx->flags >> 8) & 15, sk_for(ctx, ck.s), ck.s);
             if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "fp8 gate/up+swiglu launch: %s", hipGetErrorString(e_));
             return (int)ISO_OK;
         }));
@@ -702,7 +702,8 @@ int iso_gemm_fp8(iso_ctx *ctx, const void *a8, const float *sa, const void *w8, 
     if (ctx->cfg.dtype != ISO_BF16) return fail(ISO_ERR_DTYPE, "the FP8 GEMM writes bf16");
     if (!iso_gemm_fp8_supported(M, N, K)) return fail(ISO_ERR_SHAPE, "M=%d N=%d K=%d: need M >= 1, N %% 8 == 0, K %% 128 == 0", M, N, K);
     Timed t_(ctx, ISO_K_GEMM_O, (hipStream_t)stream);
-    hipError_t e = iso_launch_gemm_fp8(a8, sa, w8, sw, c, M, N, K, (hipStream_t)stream);
+    hipError_t e = iso_launch_gemm_fp8(a8, sa, w8, sw, c, M, N, K, (ctx->flags >> 8) & 15, sk_for(ctx, (hipStream_t)stream),
+                                       (hipStream_t)stream);
     if (e != hipSuccess) return fail(ISO_ERR_HIP, "fp8 gemm launch: %s", hipGetErrorString(e));
     return ISO_OK;
 }

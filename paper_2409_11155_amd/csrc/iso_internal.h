@@ -86,9 +86,11 @@ hipError_t iso_launch_rmsnorm_fp8(const void *x, const void *delta_or_null, void
                                   float *q_scale, int T, int H, float eps, int x_in_f32, int x_out_f32, hipStream_t s);
 hipError_t iso_launch_quant_rows_fp8(const void *x, void *q, float *scale, int rows, int cols, hipStream_t s);
 hipError_t iso_launch_gemm_fp8(const void *a8, const float *sa, const void *w8, const float *sw, void *c, int M, int N,
-                               int K, hipStream_t s);
+                               int K, int variant, iso_sk_ws *sk_or_null, hipStream_t s);
 hipError_t iso_launch_gemm_swiglu_fp8(const void *a8, const float *sa, const void *w8, const float *sw, void *act, int M,
-                                      int F, int K, hipStream_t s);
+                                      int F, int K, int variant, iso_sk_ws *sk_or_null, hipStream_t s);
+// stream-K launch shape for nk k-slices (team size, grid, grouped mapping); returns the k-slices per team
+long long iso_gemm_sk_plan(int M, int N, int nk, int num_wg, int *team, int *grid, int *grouped);
 hipError_t iso_launch_attn_simple(int dtype, const void *q, const void *k, const void *v, void *out, int Tc,
                                   int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
 hipError_t iso_launch_attn_bf16_mfma(const void *q, const void *k, const void *v, void *out, int Tc,

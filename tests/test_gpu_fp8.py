@@ -53,18 +53,21 @@ FP8_GEMM_SHAPES = [(1, 8, 128), (128, 128, 128), (129, 136, 256), (300, 264, 102
                    (1024, 4992, 6656), (260, 8, 128)]
 
 
+@pytest.mark.parametrize("flags", [0, 6 << 8])          # 6 << 8: the stream-K launch, forced
 @pytest.mark.parametrize("M,N,K", FP8_GEMM_SHAPES)
-def test_gemm_fp8(M, N, K):
+def test_gemm_fp8(M, N, K, flags):
     dt = "bf16"
     a = iso_inputs.randn((M, K), seed=M + N + K, dtype=dt)
     w = iso_inputs.randn((N, K), seed=M + N + K + 1, dtype=dt, scale=K ** -0.5)
     with make_ctx(256, 4, 4, 64, 64, dt, 256) as ctx:
+        ctx.set_flags(flags)
         a8, sa = iso.DeviceArray((M, K), "u8"), iso.DeviceArray((M,), "f32")
         w8, sw = iso.DeviceArray((N, K), "u8"), iso.DeviceArray((N,), "f32")
         ctx.quantize_rows_fp8(dev(a, dt), M, K, a8, sa, ctx.stream0)
         ctx.quantize_rows_fp8(dev(w, dt), N, K, w8, sw, ctx.stream0)
         c = iso.DeviceArray((M, N), dt, fill_byte=NAN_BYTE)
-        ctx.gemm_fp8(a8, sa, w8, sw, c, M, N, K, ctx.stream0)
+        for _ in range(3 if flags else 1):                 # stream-K: the workspace flags carry over between launches
+            ctx.gemm_fp8(a8, sa, w8, sw, c, M, N, K, ctx.stream0)
         ctx.sync()
         ref = orc.linear_fp8(h64(a, dt), h64(w, dt))       # same inputs, same quantiser: only rounding order differs
         assert orc.max_rel_err(f64(c), ref) <= TOL_STEP[dt]
@@ -87,11 +90,12 @@ def test_fp8_entry_points_reject_bad_arguments():
         assert ei.value.code == iso.ISO_ERR_DTYPE
 
 
+@pytest.mark.parametrize("sk", [0, 6 << 8])             # 6 << 8: every projection through the stream-K launch
 @pytest.mark.parametrize("hidden,nq,nkv,ffn,T,splits", [
     (512, 4, 1, 768, 300, (0, 130)),        # GQA, ragged rows
     (384, 3, 3, 256, 257, (128,)),          # MHA, odd head count
 ])
-def test_small_bf16_layer_with_fp8_projections(hidden, nq, nkv, ffn, T, splits):
+def test_small_bf16_layer_with_fp8_projections(hidden, nq, nkv, ffn, T, splits, sk):
     d, dt = 128, "bf16"
     w = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=12, dtype=dt)
     x = iso_inputs.make_hidden(T, hidden, seed=12, dtype=dt)
@@ -100,7 +104,7 @@ def test_small_bf16_layer_with_fp8_projections(hidden, nq, nkv, ffn, T, splits):
     exact = orc.layer_unsplit(h64(x, dt), oracle_weights(w, dt), sh)
     with make_ctx(hidden, nq, nkv, d, ffn, dt, 320) as ctx:
         w_dev = ctx.add_fp8_weights(iso.upload_weights(w, dt))
-        ctx.set_flags(iso.ISO_FLAG_FP8_GEMM)
+        ctx.set_flags(iso.ISO_FLAG_FP8_GEMM | sk)
         for split in splits:
             xd = dev(x, dt)
             kc = iso.DeviceArray((320, nkv, d), dt, fill_byte=NAN_BYTE)
