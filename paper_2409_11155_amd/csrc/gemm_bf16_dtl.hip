@@ -477,14 +477,10 @@ template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE>
 hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     using Cfg = DtlCfg<BM, BN, WM, WN>;
     constexpr int LDS_BYTES = (PIPE && Cfg::W3) ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
-    static bool attr_set = false;
+    static unsigned long long lds_allowed = 0;
     auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWIGLU, PIPE, false>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), LDS_BYTES, &lds_allowed); e != hipSuccess)
+        return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     dim3 grid(tiles_m * tiles_n), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
@@ -502,14 +498,10 @@ template <bool SWIGLU>
 hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K, iso_sk_ws *sk, hipStream_t s) {
     using Cfg = DtlCfg<256, 256, 4, 2>;
     constexpr int LDS_BYTES = Cfg::W3 ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
-    static bool attr_set = false;
+    static unsigned long long lds_allowed = 0;
     auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, SWIGLU, true, true>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), LDS_BYTES, &lds_allowed); e != hipSuccess)
+        return e;
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     int TS, G, grouped;
     sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped);

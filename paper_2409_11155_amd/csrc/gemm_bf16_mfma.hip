@@ -154,14 +154,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(const bf16_t *__res
 template <int BM, int BN, int BK>
 hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     using Cfg = GemmCfg<BM, BN, BK>;
-    static bool attr_set = false;   // per process; the attribute is per function and device-independent here
+    static unsigned long long lds_allowed = 0;
     auto kern = gemm_bf16_mfma_kernel<BM, BN, BK>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), (int)Cfg::LDS_BYTES, &lds_allowed); e != hipSuccess)
+        return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     dim3 grid(tiles_m * tiles_n), block(256);
     hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,

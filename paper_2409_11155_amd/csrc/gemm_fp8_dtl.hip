@@ -430,14 +430,10 @@ template <int BM, int BN, int WM, int WN, bool SWIGLU>
 hipError_t launch(const void *a, const void *w, const float *sa, const float *sw, void *c, int M, int N, int K,
                   hipStream_t s) {
     using Cfg = F8Cfg<BM, BN, WM, WN>;
-    static bool attr_set = false;
+    static unsigned long long lds_allowed = 0;
     auto kern = gemm_fp8_dtl_kernel<BM, BN, WM, WN, SWIGLU, false>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), Cfg::LDS_BYTES, &lds_allowed); e != hipSuccess)
+        return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     dim3 grid(tiles_m * tiles_n), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, s, (const unsigned char *)a, (const unsigned char *)w, sa, sw,
@@ -450,14 +446,10 @@ template <bool SWIGLU>
 hipError_t launch_sk(const void *a, const void *w, const float *sa, const float *sw, void *c, int M, int N, int K,
                      iso_sk_ws *sk, hipStream_t s) {
     using Cfg = F8Cfg<256, 256, 4, 2>;
-    static bool attr_set = false;
+    static unsigned long long lds_allowed = 0;
     auto kern = gemm_fp8_dtl_kernel<256, 256, 4, 2, SWIGLU, true>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), Cfg::LDS_BYTES, &lds_allowed); e != hipSuccess)
+        return e;
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     int TS, G, grouped;
     iso_gemm_sk_plan(M, N, K / KE, sk->num_wg, &TS, &G, &grouped);

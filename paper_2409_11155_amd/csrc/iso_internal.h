@@ -112,6 +112,19 @@ __device__ __forceinline__ float iso_wave_sum(float v) {
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
 }
+// Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the function on the device that is
+// current when it is set).  `done` is the caller's static mask of devices already served; ids beyond 63 are set every
+// time.  Called from launchers only.
+inline hipError_t iso_allow_lds(const void *kernel, int bytes, unsigned long long *done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && ((*done >> dev) & 1ull)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) *done |= 1ull << dev;
+    return e;
+}
+
 __device__ __forceinline__ float iso_wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
