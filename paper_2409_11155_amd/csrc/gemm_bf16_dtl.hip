@@ -301,9 +301,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
             // only this wave reads what it wrote: LDS accesses of one wave are ordered, no barrier needed
             constexpr int CPR = Cfg::WTN / 8;        // 16-byte pieces per row
             constexpr int PIECES = Cfg::WTM * CPR;
+            static_assert(PIECES % 64 == 0, "whole wave-stores");
             const int gm0 = m0 + wm * Cfg::WTM, gn0 = n0 + wn * Cfg::WTN;
 #pragma unroll
-            for (int p = lane; p < PIECES; p += 64) {
+            for (int it = 0; it < PIECES / 64; ++it) {
+                const int p = lane + it * 64;
                 const int row = p / CPR, cc = (p % CPR) * 8;
                 const int gm = gm0 + row, gn = gn0 + cc;
                 if (gm < M && gn < N)                // N % 8 == 0: a piece is entirely inside or outside
@@ -327,9 +329,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                     }
             constexpr int CPR = HW / 8;
             constexpr int PIECES = Cfg::WTM * CPR;
+            static_assert(PIECES % 64 == 0, "whole wave-stores");
             const int gm0 = m0 + wm * Cfg::WTM, gf0 = tile_n * (BN / 2) + wn * HW;
 #pragma unroll
-            for (int p = lane; p < PIECES; p += 64) {
+            for (int it = 0; it < PIECES / 64; ++it) {
+                const int p = lane + it * 64;
                 const int row = p / CPR, cc = (p % CPR) * 8;
                 const int gm = gm0 + row, gf = gf0 + cc;
                 if (gm < M && gf < F)                // F % 8 == 0

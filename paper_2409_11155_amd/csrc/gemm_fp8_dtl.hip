@@ -266,9 +266,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_fp8_dtl_kernel(const unsign
             }
             constexpr int CPR = Cfg::WTN / 8;
             constexpr int PIECES = Cfg::WTM * CPR;
+            static_assert(PIECES % 64 == 0, "whole wave-stores");
             const int gm0 = m0 + wm * Cfg::WTM, gn0 = n0 + wn * Cfg::WTN;
 #pragma unroll
-            for (int p = lane; p < PIECES; p += 64) {
+            for (int it = 0; it < PIECES / 64; ++it) {
+                const int p = lane + it * 64;
                 const int row = p / CPR, cc = (p % CPR) * 8;
                 const int gm = gm0 + row, gn = gn0 + cc;
                 if (gm < M && gn < N)
@@ -297,9 +299,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_fp8_dtl_kernel(const unsign
             }
             constexpr int CPR = HW / 8;
             constexpr int PIECES = Cfg::WTM * CPR;
+            static_assert(PIECES % 64 == 0, "whole wave-stores");
             const int gm0 = m0 + wm * Cfg::WTM;
 #pragma unroll
-            for (int p = lane; p < PIECES; p += 64) {
+            for (int it = 0; it < PIECES / 64; ++it) {
+                const int p = lane + it * 64;
                 const int row = p / CPR, cc = (p % CPR) * 8;
                 const int gm = gm0 + row, gf = gf0 + cc;
                 if (gm < M && gf < F)
