@@ -225,6 +225,40 @@ def test_attn_chunk_mid_size_launch_takes_two_row_blocks_per_workgroup(Tc, q_off
         assert err <= tol, (err, tol)
 
 
+@pytest.mark.parametrize("Tc,q_offset", [(53248, 77824), (77824, 0)])
+def test_attn_chunk_full_size_deep_in_a_128k_cache_sampled_rows(Tc, q_offset):
+    """Both chunks of the 128k prompt cut at 77824 (70B, TP=8: 8 query heads on 1 KV head) at their real size and in
+    the launch shape the library picks for them (3328 and 4864 row blocks: one per workgroup, two workgroups per
+    compute unit).  The oracle takes the sampled rows one query at a time."""
+    dt, d, nq, nkv = "bf16", 128, 8, 1
+    kv_len = q_offset + Tc
+    q, k, v = iso_inputs.make_qkv_cache(Tc, kv_len, nq, nkv, d, seed=128, dtype=dt)
+    with make_ctx(256, nq, nkv, d, 64, dt, kv_len) as ctx:
+        out = iso.DeviceArray((Tc, nq * d), dt, fill_byte=NAN_BYTE)
+        ctx.attn_chunk(dev(q, dt), dev(k, dt), dev(v, dt), out, Tc, q_offset, kv_len, ctx.stream0)
+        ctx.sync()
+        got = f64(out)
+    assert np.isfinite(got).all()
+    gen = np.random.default_rng(7)
+    rows = sorted({0, 1, 127, 128, Tc - 129, Tc - 128, Tc - 1} | set(int(r) for r in gen.integers(0, Tc, 25)))
+    k64, v64 = h64(k, dt), h64(v, dt)
+    # A row averages ~1e5 values, so its output is small against max|v| and the worst-case bound of the short cases
+    # (a multiple of max|v| / rms) says nothing here.  What the arithmetic gives, relative to the row's rms: the bf16
+    # rounding of the output is at most 2^-8 of an element, hence 2^-8 max|ref| / rms; the bf16 rounding of the
+    # probabilities puts independent relative errors of at most 2^-8 on the terms of a sum whose own root-mean-square
+    # is the row's rms, i.e. a standard deviation of at most 2^-8 / sqrt(3) of it, six of which cover every compared
+    # element.  (About 0.03 for a row whose largest element is 4 rms; gross for any indexing mistake at this size.)
+    worst = 0.0
+    for i in rows:
+        ref = orc.attention_chunk(h64(q[i:i + 1], dt), k64, v64, q_offset + i, kv_len).reshape(nq * d)
+        rms = float(np.sqrt(np.mean(ref * ref)))
+        tol = 2.0 ** -8 * float(np.abs(ref).max()) / rms + 6.0 * 2.0 ** -8 / np.sqrt(3.0)
+        err = float(np.abs(got[i] - ref).max() / rms)
+        worst = max(worst, err / tol)
+        assert err <= tol, (i, err, tol)
+    print(f"deep-cache attention: worst row at {worst:.2f} of its bound over {len(rows)} rows")
+
+
 def test_attn_chunk_rejects_bad_arguments():
     with make_ctx(256, 4, 4, 64, 64, "f32", 64) as ctx:
         t = iso.DeviceArray((64, 256), "f32", fill_byte=0)
