@@ -60,8 +60,10 @@ __device__ __forceinline__ float half_swap_max(float v) {
 // of the row block's key tiles and waves 4-7 the second half, each group with its own LDS stages, and the two partial
 // results (running maximum, sum and unnormalised output of every row) are merged through LDS at the end.  That
 // halves the serial chain of tiles of a row block and puts two waves on every SIMD, so the softmax arithmetic of one
-// overlaps the matrix instructions of the other.
-template <int NSTAGE, int KVS>
+// overlaps the matrix instructions of the other.  SKEW (with KVS = 2): the second group runs one phase behind the
+// first (its second product is deferred to the next iteration), so that the two waves of a SIMD, which leave every
+// barrier together, do not ask for the same pipe at the same time (measured 2-5 %).
+template <int NSTAGE, int KVS, bool SKEW>
 __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_kernel(const bf16_t *__restrict__ Q,
                                                             const bf16_t *__restrict__ Kc,
                                                             const bf16_t *__restrict__ Vc,
@@ -170,104 +172,92 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
     const int half = (n_tiles_all + KVS - 1) / KVS;
     const int t_lo = kgrp * half;
     const int n_tiles = max(0, min(half, n_tiles_all - t_lo));
-    const int n_iter = KVS == 1 ? n_tiles : half;
+    // SKEW: the second group is one phase behind (see below) and needs one iteration more than it has tiles
+    const int n_iter = KVS == 1 ? n_tiles : (SKEW ? max(half, n_tiles_all - half + 1) : half);
 
-#pragma unroll
-    for (int p = 0; p < NSTAGE - 1; ++p)
-        if (p < n_tiles) issue(p, (t_lo + p) * BN);
     // Tiles that lie entirely at or below the diagonal of the block's first row and inside the cache need neither
     // a mask nor a per-wave skip: they run a branch-free body.  The few tiles that touch the diagonal or the end of
     // the cache (and the idle iterations of the shorter key group) take the general body.
     const int n_plain_all = min((q_offset + m0 + 1) / BN, kv_len / BN);
     const int n_main = max(0, min(n_plain_all - t_lo, n_tiles));
-    static_assert(NSTAGE == 2, "the branch-free body requests tile jt+1 while tile jt is multiplied: two stages");
-    auto tile = [&](int jt, auto tail_c) {
-        constexpr bool TAIL = decltype(tail_c)::value;
-        const int j0 = (t_lo + jt) * BN;
-        // this wave's loads of tile jt have landed: in steady state the NSTAGE-2 younger tiles (8 loads each)
-        // may still be in flight; near the end fewer are outstanding, so wait for everything
-        if (NSTAGE > 2 && jt + NSTAGE - 2 < n_tiles)
-            __builtin_amdgcn_s_waitcnt(0x0F70 | ((8 * (NSTAGE - 2)) & 15) | (((8 * (NSTAGE - 2)) >> 4) << 14));
-        else
-            __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();                    // ... everyone's have, and tile jt-1 is no longer being read
-        // Requests for the next tile.  In the branch-free body they are issued between the MFMAs of the first product
-        // (below); issued in one burst here they hold the wave for some 500 cycles.
-        if (TAIL && jt + NSTAGE - 1 < n_tiles) issue((jt + NSTAGE - 1) % NSTAGE, j0 + (NSTAGE - 1) * BN);
-        if (TAIL) {
-            if (KVS > 1 && jt >= n_tiles) return;   // the shorter group idles through the last barrier
-            if (j0 > wave_q_max) return;            // every key of this tile is above this wave's diagonal
-        }
-        const unsigned char *kb = lds_g + (jt % NSTAGE) * STAGE_B;
+    static_assert(NSTAGE == 2, "tile jt+1 is requested while tile jt is multiplied: two stages");
 
-        // --- S^T = K Q^T for two 32-key blocks.  The 16 K fragments are fetched four at a time, one group ahead of
-        //     the MFMAs that use them (left to itself the compiler issues every LDS read right before its MFMA and
-        //     the matrix pipe waits out the LDS latency sixteen times per tile).
-        f32x16_t s[2];
+    // this wave's loads have landed, everyone's have, and the stages of the previous iteration are no longer read
+    auto wait_and_sync = [&]() {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
+
+    // --- S^T = K Q^T of tile jt (K stage jt % 2) for two 32-key blocks.  The 16 K fragments are fetched four at a
+    //     time, one group ahead of the MFMAs that use them (left to itself the compiler issues every LDS read right
+    //     before its MFMA and the matrix pipe waits out the LDS latency sixteen times per tile).  WEAVE: once the last
+    //     K fragment reads are out (LDS writes keep their order against LDS reads), requests(0) and requests(1) -- four
+    //     global -> LDS loads each -- go one load behind each MFMA of the third and fourth group; issued in one burst
+    //     at the top of the tile they hold the wave for some 500 cycles.
+    auto qk_scores = [&](int jt, f32x16_t (&sc_t)[2], auto weave_c, auto &&requests) {
+        constexpr bool WEAVE = decltype(weave_c)::value;
+        const unsigned char *kb = lds_g + (jt % NSTAGE) * STAGE_B;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
-        {
-            bf16x8_t kf[2][4];
-            auto read_k = [&](int buf, int grp) {          // group = (sub, half of the head dim): 4 k-steps
-                const int sub = grp >> 1, ks0 = (grp & 1) * 4;
+            for (int r = 0; r < 16; ++r) sc_t[sub][r] = 0.f;
+        bf16x8_t kf[2][4];
+        auto read_k = [&](int buf, int grp) {          // group = (sub, half of the head dim): 4 k-steps
+            const int sub = grp >> 1, ks0 = (grp & 1) * 4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    kf[buf][i] = *reinterpret_cast<const bf16x8_t *>(kb + sub * 32 * ROW_B + k_row_off +
-                                                                    (((2 * (ks0 + i) + lgrp) ^ k_sw) << 4));
-            };
-            read_k(0, 0);
+            for (int i = 0; i < 4; ++i)
+                kf[buf][i] = *reinterpret_cast<const bf16x8_t *>(kb + sub * 32 * ROW_B + k_row_off +
+                                                                (((2 * (ks0 + i) + lgrp) ^ k_sw) << 4));
+        };
+        read_k(0, 0);
 #pragma unroll
-            for (int grp = 0; grp < 4; ++grp) {
-                if (grp + 1 < 4) read_k((grp + 1) & 1, grp + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                const int sub = grp >> 1, ks0 = (grp & 1) * 4;
+        for (int grp = 0; grp < 4; ++grp) {
+            if (grp + 1 < 4) read_k((grp + 1) & 1, grp + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            const int sub = grp >> 1, ks0 = (grp & 1) * 4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[grp & 1][i], qf[ks0 + i], s[sub], 0, 0, 0);
-                if (!TAIL && grp >= 2) {
-                    // Once the last K fragment reads are out (LDS writes keep their order against LDS reads), the
-                    // eight requests for tile jt+1 go one behind each remaining MFMA: K with the third group, V with
-                    // the fourth.  No test for the end of the range: a tile past this group's share is never used, its
-                    // stage is free, and rows past the cache read as zero.
-                    issue_half((jt + 1) % NSTAGE, j0 + BN, grp - 2);
+            for (int i = 0; i < 4; ++i)
+                sc_t[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[grp & 1][i], qf[ks0 + i], sc_t[sub], 0, 0, 0);
+            if (WEAVE && grp >= 2) {
+                requests(grp - 2);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                    }
+                for (int i = 0; i < 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // --- mask (only tiles that touch the diagonal or the end of the cache).  The scores stay unscaled: the
-        //     softmax scale is positive, so the running maximum can be kept in raw units and the scale folded
-        //     into the exponent's multiply-add.
+    };
+
+    // --- mask (only tiles that touch the diagonal or the end of the cache), running maximum and sum, probabilities.
+    //     The scores stay unscaled: the softmax scale is positive, so the running maximum can be kept in raw units and
+    //     the scale folded into the exponent's multiply-add.
+    auto softmax = [&](int j0, auto tail_c, f32x16_t (&sc_t)[2], bf16x8_t (&pb)[2][2]) {
+        constexpr bool TAIL = decltype(tail_c)::value;
         if (TAIL && ((j0 + BN - 1 > q_offset + m0 + wave * 32) || (j0 + BN > kv_len))) {
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = j0 + sub * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4);
-                    if (key > q_abs || key >= kv_len) s[sub][r] = -INFINITY;
+                    if (key > q_abs || key >= kv_len) sc_t[sub][r] = -INFINITY;
                 }
         }
         float mx = -INFINITY;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc_t[sub][r]);
         mx = half_swap_max(mx);
         const float m_new = fmaxf(m_run, mx);
         const float neg_m = -m_new * sc;
         float psum = 0.f;
-        bf16x8_t pb[2][2];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][r], sc, neg_m));
+                const float p = __builtin_amdgcn_exp2f(fmaf(sc_t[sub][r], sc, neg_m));
                 psum += p;
                 pb[sub][r / 8][r % 8] = (bf16_t)p;
             }
@@ -283,40 +273,100 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
                 for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
         }
         l_run += psum;
-        // --- O^T += V^T P^T.  k-slots 8*lgrp .. +8 of MFMA step (sub, t) hold keys
-        //     32 sub + 16 t + 4 lgrp + {0..3} and 32 sub + 16 t + 8 + 4 lgrp + {0..3}: two transposing reads.
-        //     The V fragments of one 32-dim block (4 MFMAs) are fetched while the previous block is multiplied.
-        {
-            bf16x8_t vf[2][4];
-            const uint32_t vb_addr = lds_addr + (uint32_t)((jt % NSTAGE) * STAGE_B + TILE_B + v_row_base * ROW_B + v_byte);
-            auto read_v = [&](int buf, int dt) {
-                const uint32_t a = vb_addr + (uint32_t)(((4 * dt + v_chunk_base) ^ v_sw) << 4);
-                // MFMA step st = (sub, t) takes key rows 32 sub + 16 t + {0, 8} (+ the lane's row inside the block)
-                vf[buf][0] = __builtin_shufflevector(lds_read_tr16<0 * ROW_B>(a), lds_read_tr16<8 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
-                vf[buf][1] = __builtin_shufflevector(lds_read_tr16<16 * ROW_B>(a), lds_read_tr16<24 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
-                vf[buf][2] = __builtin_shufflevector(lds_read_tr16<32 * ROW_B>(a), lds_read_tr16<40 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
-                vf[buf][3] = __builtin_shufflevector(lds_read_tr16<48 * ROW_B>(a), lds_read_tr16<56 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
-            };
-            read_v(0, 0);
+    };
+
+    // --- O^T += V^T P^T with V tile vt (V stage vt % 2).  k-slots 8*lgrp .. +8 of MFMA step (sub, t) hold keys
+    //     32 sub + 16 t + 4 lgrp + {0..3} and 32 sub + 16 t + 8 + 4 lgrp + {0..3}: two transposing reads.
+    //     The V fragments of one 32-dim block (4 MFMAs) are fetched while the previous block is multiplied.
+    auto pv = [&](int vt, bf16x8_t (&pb)[2][2]) {
+        bf16x8_t vf[2][4];
+        const uint32_t vb_addr = lds_addr + (uint32_t)((vt % NSTAGE) * STAGE_B + TILE_B + v_row_base * ROW_B + v_byte);
+        auto read_v = [&](int buf, int dt) {
+            const uint32_t a = vb_addr + (uint32_t)(((4 * dt + v_chunk_base) ^ v_sw) << 4);
+            // MFMA step st = (sub, t) takes key rows 32 sub + 16 t + {0, 8} (+ the lane's row inside the block)
+            vf[buf][0] = __builtin_shufflevector(lds_read_tr16<0 * ROW_B>(a), lds_read_tr16<8 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+            vf[buf][1] = __builtin_shufflevector(lds_read_tr16<16 * ROW_B>(a), lds_read_tr16<24 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+            vf[buf][2] = __builtin_shufflevector(lds_read_tr16<32 * ROW_B>(a), lds_read_tr16<40 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+            vf[buf][3] = __builtin_shufflevector(lds_read_tr16<48 * ROW_B>(a), lds_read_tr16<56 * ROW_B>(a), 0, 1, 2, 3, 4, 5, 6, 7);
+        };
+        read_v(0, 0);
 #pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt) {
-                if (dt + 1 < D / 32) {
-                    read_v((dt + 1) & 1, dt + 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    lds_tr_wait<8>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);   // 8 younger reads may pend
-                } else {
-                    __builtin_amdgcn_sched_barrier(0);
-                    lds_tr_wait<0>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);
-                }
-#pragma unroll
-                for (int st = 0; st < 4; ++st)
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt & 1][st], pb[st >> 1][st & 1], o[dt], 0, 0, 0);
+        for (int dt = 0; dt < D / 32; ++dt) {
+            if (dt + 1 < D / 32) {
+                read_v((dt + 1) & 1, dt + 1);
                 __builtin_amdgcn_sched_barrier(0);
+                lds_tr_wait<8>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);   // 8 younger reads may pend
+            } else {
+                __builtin_amdgcn_sched_barrier(0);
+                lds_tr_wait<0>(vf[dt & 1][0], vf[dt & 1][1], vf[dt & 1][2], vf[dt & 1][3]);
             }
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt & 1][st], pb[st >> 1][st & 1], o[dt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
-    for (int jt = 0; jt < n_main; ++jt) tile(jt, std::false_type{});
-    for (int jt = n_main; jt < n_iter; ++jt) tile(jt, std::true_type{});
+
+    if (!(SKEW && KVS > 1) || kgrp == 0) {
+        // One tile per iteration: scores, softmax, second product.  In the branch-free body the eight requests for
+        // tile jt+1 ride behind the MFMAs of the first product (no test for the end of the range: a tile past this
+        // group's share is never used, its stage is free, and rows past the cache read as zero).
+        auto tile = [&](int jt, auto tail_c) {
+            constexpr bool TAIL = decltype(tail_c)::value;
+            const int j0 = (t_lo + jt) * BN;
+            wait_and_sync();
+            if (TAIL && jt + 1 < n_tiles) issue((jt + 1) % NSTAGE, j0 + BN);
+            if (TAIL) {
+                if (KVS > 1 && jt >= n_tiles) return;   // idle iterations: the other group has more to do
+                if (j0 > wave_q_max) return;            // every key of this tile is above this wave's diagonal
+            }
+            f32x16_t sc_t[2];
+            bf16x8_t pb[2][2];
+            qk_scores(jt, sc_t, std::integral_constant<bool, !TAIL>{},
+                      [&](int which) { issue_half((jt + 1) % NSTAGE, j0 + BN, which); });
+            softmax(j0, tail_c, sc_t, pb);
+            pv(jt, pb);
+        };
+        if (0 < n_tiles) issue(0, t_lo * BN);
+        for (int jt = 0; jt < n_main; ++jt) tile(jt, std::false_type{});
+        for (int jt = n_main; jt < n_iter; ++jt) tile(jt, std::true_type{});
+    } else {
+        // The second key group runs one phase behind: iteration jt does the SECOND product of tile jt-1 and then the
+        // scores and softmax of tile jt.  Waves w and w+4 of a 512-thread workgroup share a SIMD (one from each group)
+        // and leave every barrier together; with the same order of phases both would want the matrix pipe and then
+        // both the vector ALU.  Shifted, one group's softmax runs under the other group's MFMAs.  Same arithmetic in
+        // the same order as the plain loop, so the results are bit-identical.
+        // K tile jt+1 and V tile jt are requested in iteration jt: V stage jt % 2 was last read (tile jt-2) in
+        // iteration jt-1, K stage (jt+1) % 2 (tile jt-1) likewise.
+        bf16x8_t pb[2][2];
+        bool have_p = false;                            // wave-uniform
+        auto tile = [&](int jt, auto tail_c) {
+            constexpr bool TAIL = decltype(tail_c)::value;
+            const int j0 = (t_lo + jt) * BN;
+            wait_and_sync();
+            f32x16_t sc_t[2];
+            if (TAIL) {
+                if (jt + 1 < n_tiles) issue_half((jt + 1) % NSTAGE, j0 + BN, 0);
+                if (jt < n_tiles) issue_half(jt % NSTAGE, j0, 1);
+                if (have_p) pv(jt - 1, pb);
+                have_p = false;
+                if (jt >= n_tiles || j0 > wave_q_max) return;
+                qk_scores(jt, sc_t, std::false_type{}, [](int) {});
+            } else {
+                pv(jt - 1, pb);
+                qk_scores(jt, sc_t, std::true_type{}, [&](int which) {
+                    if (which == 0) issue_half((jt + 1) % NSTAGE, j0 + BN, 0);
+                    else issue_half(jt % NSTAGE, j0, 1);
+                });
+            }
+            softmax(j0, tail_c, sc_t, pb);
+            have_p = true;
+        };
+        if (0 < n_tiles) issue_half(0, t_lo * BN, 0);
+        tile(0, std::true_type{});
+        for (int jt = 1; jt < n_main; ++jt) tile(jt, std::false_type{});
+        for (int jt = max(1, n_main); jt < n_iter; ++jt) tile(jt, std::true_type{});
+    }
 
     if (KVS > 1) {
         // merge the two groups: group 1 parks (m, l, o) of its rows in LDS, group 0 folds them into its own.
@@ -377,10 +427,10 @@ hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v,
                                     int kv_len, int nq, int nkv, int d, int q_stride, int shape, hipStream_t s) {
     if (d != D) return hipErrorInvalidValue;
     static unsigned long long lds_allowed[2] = {0, 0};
-    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(attn_bf16_dtl_kernel<2, 1>), 2 * STAGE_B, &lds_allowed[0]);
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(attn_bf16_dtl_kernel<2, 1, false>), 2 * STAGE_B, &lds_allowed[0]);
         e != hipSuccess)
         return e;
-    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(attn_bf16_dtl_kernel<2, 2>), 2 * 2 * STAGE_B, &lds_allowed[1]);
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(attn_bf16_dtl_kernel<2, 2, true>), 2 * 2 * STAGE_B, &lds_allowed[1]);
         e != hipSuccess)
         return e;
     const int n_blocks = (Tc + BM - 1) / BM;
@@ -404,15 +454,13 @@ hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v,
     const long long rounds = (paired + ncu - 1) / ncu;
     const bool pair_ok = wgs >= 320 && wgs <= 2048 && (paired <= ncu || paired * 10 >= 9 * rounds * ncu);
     const int mode = shape >= 1 && shape <= 3 ? shape - 1 : (pair_ok ? 1 : wgs < 512 ? 0 : 2);
-    if (mode == 0)
-        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2>), dim3(n_blocks, nq), dim3(512), 2 * 2 * STAGE_B, s, (const bf16_t *)q,
-                           (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride, 0);
-    else if (mode == 1)
-        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2>), dim3((n_blocks + 1) / 2, nq), dim3(512), 2 * 2 * STAGE_B, s,
-                           (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq,
-                           nkv, q_stride, 1);
+    if (mode == 0 || mode == 1)
+        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2, true>), dim3(mode == 0 ? n_blocks : (n_blocks + 1) / 2, nq), dim3(512),
+                           2 * 2 * STAGE_B, s, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc,
+                           q_offset, kv_len, nq, nkv, q_stride, mode);
     else
-        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 1>), dim3(n_blocks, nq), dim3(256), 2 * STAGE_B, s, (const bf16_t *)q,
-                           (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride, 0);
+        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 1, false>), dim3(n_blocks, nq), dim3(256), 2 * STAGE_B, s,
+                           (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq,
+                           nkv, q_stride, 0);
     return hipGetLastError();
 }
