@@ -20,6 +20,11 @@
  *     of the calling thread.
  *   - The sum over tensor-parallel ranks is over a world of one rank: the shard's partial output is
  *     what is added to the residual stream.
+ *   - The compute entry points may be recorded into a HIP graph (stream capture on stream0; the
+ *     library's other streams join through its events) once the same call has run eagerly, so that
+ *     streams, events and kernel attributes exist.  While a stream is capturing, the stream-K GEMM
+ *     launch is not used (its launches are numbered, a replay would repeat a number) and per-launch
+ *     timing is off.
  */
 #ifndef ISO_H_
 #define ISO_H_

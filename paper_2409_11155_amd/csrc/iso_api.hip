@@ -81,13 +81,20 @@ int check_cfg(const iso_cfg *c) {
     return ISO_OK;
 }
 
-// Brackets one launch with a pair of events in the launch's own stream when timing is on.
+// True while `s` is recording into a HIP graph (or when that cannot be told).
+bool capturing(hipStream_t s) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    return hipStreamIsCapturing(s, &st) != hipSuccess || st != hipStreamCaptureStatusNone;
+}
+
+// Brackets one launch with a pair of events in the launch's own stream when timing is on (never inside a graph
+// capture: the events of a replayed graph have no elapsed time to read).
 struct Timed {
     iso_ctx *c;
     int idx;
     hipStream_t s;
     Timed(iso_ctx *ctx, int kind, hipStream_t stream) : c(ctx), idx(-1), s(stream) {
-        if (!c->timing || c->n_tev >= ISO_MAX_TIMED) return;
+        if (!c->timing || c->n_tev >= ISO_MAX_TIMED || capturing(stream)) return;
         if (c->n_tev == c->n_tev_created) {
             if (hipEventCreate(&c->tev0[c->n_tev]) != hipSuccess) return;
             if (hipEventCreate(&c->tev1[c->n_tev]) != hipSuccess) { (void)hipEventDestroy(c->tev0[c->n_tev]); return; }
@@ -106,9 +113,12 @@ inline char *at(void *base, size_t row, size_t width, size_t e) { return (char *
 inline const char *at(const void *base, size_t row, size_t width, size_t e) { return (const char *)base + row * width * e; }
 
 // Stream-K workspace for a launch on stream s: the context owns one per stream of its own, so launches that share
-// a workspace are ordered; a foreign stream gets none and takes the plain kernels.
+// a workspace are ordered; a foreign stream gets none and takes the plain kernels.  Neither does a stream that is
+// recording into a HIP graph: every stream-K launch carries its own sequence number (the flags of the workspace are
+// never reset), and a replayed graph would present the number of its first run again.
 iso_sk_ws *sk_for(iso_ctx *ctx, hipStream_t s) {
     if (((ctx->flags & ISO_FLAG_NO_STREAMK) || ctx->sk_hold) && ((ctx->flags >> 8) & 7) != 6) return nullptr;
+    if (capturing(s)) return nullptr;
     if (s == ctx->stream[0] && ctx->sk[0].base) return &ctx->sk[0];
     if (s == ctx->stream[1] && ctx->sk[1].base) return &ctx->sk[1];
     return nullptr;
