@@ -67,7 +67,7 @@ template <int BM, int BN, int WM, int WN> struct DtlCfg {
 // finishing segments (the one that needs partials last), and a finisher only ever waits for workgroups with a lower index, which the dispatcher
 // started earlier and which never wait before raising their flag: the waits always end.  They are bounded as
 // well: a wait that exceeds the spin limit reports through *sk_err and carries on.
-template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE, bool SK>
+template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE, bool SK, bool M16 = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_t *__restrict__ A,
                                                                      const bf16_t *__restrict__ W,
                                                                      bf16_t *__restrict__ C, int M, int N, int K,
@@ -85,7 +85,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS bases of the wave-loads stay scalar
     const int wm = wave / WN, wn = wave % WN;
-    const int lrow = lane & 31, lgrp = lane >> 5;
 
     // ---- global side of the direct-to-LDS loads
     const int ld_row = lane >> 3;          // row inside the 8-row wave-load
@@ -149,40 +148,58 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
         issue_w(stage, k0);
     };
 
-    // ---- LDS side: byte offsets of this lane's operand rows; the k chunk is XOR-ed in per k-step
-    int a_row_off[TM], w_row_off[TN], a_sw[TM], w_sw[TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int r = wm * Cfg::WTM + i * 32 + lrow;
-        a_row_off[i] = r * ROW_BYTES;
-        a_sw[i] = swz(r);
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int r = wn * Cfg::WTN + j * 32 + lrow;
-        w_row_off[j] = W_ORIGIN + r * ROW_BYTES;
-        w_sw[j] = swz(r);
-    }
+    // ---- LDS side: byte offsets of this lane's operand rows; the k chunk is XOR-ed in per k-step.
+    // M16: the products are issued as v_mfma_f32_16x16x32_bf16 (k-steps of 32: lane l holds row l % 16 and the 16-byte
+    // chunk l / 16 of the step) instead of 32x32x16 (k-steps of 16: row l % 32, chunk l / 32).  Same LDS tiles, same
+    // bytes read per FLOP; the smaller instruction moves a quarter of the accumulator registers per issue and
+    // measured 15 % more arithmetic per watt on random data (register-only loops: 1.91 against 1.66 PFLOP/s).
+    constexpr int MR = M16 ? 16 : 32;                       // rows / columns of one MFMA block
+    constexpr int KSTEP = M16 ? 32 : 16;                    // k per MFMA
+    constexpr int NKS = BK / KSTEP;                         // k-steps per slice
+    constexpr int FM = Cfg::WTM / MR, FN = Cfg::WTN / MR;   // operand fragments per k-step
+    const int frow = lane & (MR - 1), fgrp = lane / MR;
+    // The rows a lane reads (frow + a multiple of 16) all have the same swizzle term, and their offsets from the
+    // first one are compile-time constants: one base address per operand, the rest is instruction offsets.
+    static_assert(Cfg::WTM % 16 == 0 && Cfg::WTN % 16 == 0, "swizzle term shared by a lane's rows");
+    const int f_sw = swz(frow);
+    const int a_row0 = (wm * Cfg::WTM + frow) * ROW_BYTES, w_row0 = W_ORIGIN + (wn * Cfg::WTN + frow) * ROW_BYTES;
 
+    // Accumulators: one f32x16 per 32x32 block of the wave tile.  M16 keeps the four 16x16 sub-blocks (si, sj) of a
+    // block in registers 4 * (2 si + sj) .. + 3 of that vector.
     f32x16_t acc[TM][TN];
-    bf16x8_t af[2][TM], wf[2][TN];
+    bf16x8_t af[2][FM], wf[2][FN];
     auto read_frags2 = [&](const unsigned char *abase, const unsigned char *wbase, int buf, int ks) {
-        const int chunk = ks * 2 + lgrp;
+        const int chunk_off = ((ks * (KSTEP / 8) + fgrp) ^ f_sw) << 4;
+        const unsigned char *ap = abase + a_row0 + chunk_off, *wp = wbase + w_row0 + chunk_off;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            af[buf][i] = *reinterpret_cast<const bf16x8_t *>(abase + a_row_off[i] + ((chunk ^ a_sw[i]) << 4));
+        for (int i = 0; i < FM; ++i) af[buf][i] = *reinterpret_cast<const bf16x8_t *>(ap + i * MR * ROW_BYTES);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            wf[buf][j] = *reinterpret_cast<const bf16x8_t *>(wbase + w_row_off[j] + ((chunk ^ w_sw[j]) << 4));
+        for (int j = 0; j < FN; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8_t *>(wp + j * MR * ROW_BYTES);
     };
     auto read_frags = [&](const unsigned char *base, int buf, int ks) { read_frags2(base, base, buf, ks); };
     auto mfma_step = [&](int buf) {
+        if constexpr (M16) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], wf[buf][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < FN; ++j) {
+                    f32x16_t &blk = acc[i / 2][j / 2];
+                    const int q = 4 * (2 * (i & 1) + (j & 1));
+                    f32x4_t sub = {blk[q], blk[q + 1], blk[q + 2], blk[q + 3]};
+                    sub = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[buf][i], wf[buf][j], sub, 0, 0, 0);
+                    blk[q] = sub[0]; blk[q + 1] = sub[1]; blk[q + 2] = sub[2]; blk[q + 3] = sub[3];
+                }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], wf[buf][j], acc[i][j], 0, 0, 0);
+        }
     };
+    // Row and column, inside its 32x32 block, of accumulator register r of this lane.
+    auto blk_row = [&](int r) { return M16 ? 16 * (r / 8) + 4 * fgrp + (r % 4) : 8 * (r / 4) + 4 * fgrp + (r % 4); };
+    auto blk_col = [&](int r) { return M16 ? 16 * ((r / 4) & 1) + frow : frow; };
 
     // ---- k slices [kb, ke) of the current tile into acc
     auto run = [&](int kb, int ke) {
@@ -204,7 +221,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
             for (int kt = 0; kt < n; ++kt) {
                 const unsigned char *base = lds + (kt & 1) * STAGE;
 #pragma unroll
-                for (int ks = 0; ks < BK / 16 - 1; ++ks) {
+                for (int ks = 0; ks < NKS - 1; ++ks) {
                     read_frags(base, (ks + 1) & 1, ks + 1);
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_step(ks & 1);
@@ -217,7 +234,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                     if (kt + 2 < n) issue(kt & 1, (kb + kt + 2) * BK);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                mfma_step((BK / 16 - 1) & 1);
+                mfma_step((NKS - 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
@@ -225,7 +242,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
             // hand-over step, the direct-to-LDS loads two slices ahead) are slotted between the MFMAs, one
             // memory instruction per MFMA, so a wave's memory issue runs in the shadow of its own matrix
             // instructions instead of leaving the matrix pipe idle.
-            constexpr int NMFMA = TM * TN, NREAD = TM + TN, NLOAD = A_LOADS + W_LOADS;
+            constexpr int NMFMA = FM * FN, NREAD = FM + FN, NLOAD = A_LOADS + W_LOADS;
             auto weave = [&](bool with_loads) {
 #pragma unroll
                 for (int i = 0; i < NREAD; ++i) {
@@ -252,7 +269,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                 const int wnx = wst + 1 == WS ? 0 : wst + 1;
                 const unsigned char *abase = lds + (kt & 1) * A_STRIDE, *wbase = lds + wst * W_STRIDE;
 #pragma unroll
-                for (int ks = 0; ks < BK / 16 - 1; ++ks) {
+                for (int ks = 0; ks < NKS - 1; ++ks) {
                     read_frags2(abase, wbase, (ks + 1) & 1, ks + 1);
                     mfma_step(ks & 1);
                     weave(false);
@@ -272,7 +289,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                         else issue_w(kt & 1, (kb + kt + 2) * BK);
                     }
                 }
-                mfma_step((BK / 16 - 1) & 1);
+                mfma_step((NKS - 1) & 1);
                 if (handover) weave(more);
                 __builtin_amdgcn_sched_barrier(0);
                 wst = wnx;
@@ -296,7 +313,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * Cfg::CP + j * 32 + lrow] =
+                        ct[(i * 32 + blk_row(r)) * Cfg::CP + j * 32 + blk_col(r)] =
                             (bf16_t)acc[i][j][r];
             // only this wave reads what it wrote: LDS accesses of one wave are ordered, no barrier needed
             constexpr int CPR = Cfg::WTN / 8;        // 16-byte pieces per row
@@ -325,7 +342,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                     for (int r = 0; r < 16; ++r) {
                         const float g = acc[i][2 * jp][r], u = acc[i][2 * jp + 1][r];
                         const float a = g / (1.0f + __expf(-g)) * u;
-                        ct[(i * 32 + 8 * (r / 4) + 4 * lgrp + (r % 4)) * HP + jp * 32 + lrow] = (bf16_t)a;
+                        ct[(i * 32 + blk_row(r)) * HP + jp * 32 + blk_col(r)] = (bf16_t)a;
                     }
             constexpr int CPR = HW / 8;
             constexpr int PIECES = Cfg::WTM * CPR;
@@ -477,12 +494,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
 #endif
 }
 
-template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE>
+template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE, bool M16 = false>
 hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     using Cfg = DtlCfg<BM, BN, WM, WN>;
     constexpr int LDS_BYTES = (PIPE && Cfg::W3) ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
     static unsigned long long lds_allowed = 0;
-    auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWIGLU, PIPE, false>;
+    auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWIGLU, PIPE, false, M16>;
     if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), LDS_BYTES, &lds_allowed); e != hipSuccess)
         return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
@@ -564,8 +581,14 @@ static int pick_variant(int M, int N) {
 // in L2: 1024x4992x6656 at 32 slices per team +13 %, 2048x1280x8192 at 20 +29 %, 2048x8192x1024 at 16 even); with less
 // k depth the cost of parking and fetching the partial tiles (about 6 us per workgroup) dominates (1024x6656x1664 at
 // 11 slices per team: 52 against 37 us).
+// Not when whole 256x256 tiles already fill their rounds of the chip to 85 %: there the tile-per-workgroup launch with
+// 16x16x32 MFMAs is ahead or even (4096x8192x7168 353 against 369 us, 8192x7168x8192 719 against 742, 2048x7168x8192
+// at 224 tiles 196 against 207; 4096x2560x8192 at 160 tiles 179 against 156 the other way).
 static bool sk_wanted(int M, int N, int K, const iso_sk_ws *sk) {
     if (!sk || !sk->base || sk->num_wg < 8) return false;
+    const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    const long long rounds = (tiles + sk->num_wg - 1) / sk->num_wg;
+    if (tiles * 100 >= 85 * rounds * sk->num_wg) return false;
     int TS, G, grouped;
     return sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped) >= 20 && grouped;
 }
@@ -603,7 +626,9 @@ hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M
     return plain ? launch<BM_, BN_, WM_, WN_, false, false>(a, w, c, M, N, K, s)          \
                  : launch<BM_, BN_, WM_, WN_, false, true>(a, w, c, M, N, K, s)
     switch (v) {
-        case 1: ISO_DTL(256, 256, 4, 2);
+        case 1:   // the interleaved loop of the full-size tile issues its products as 16x16x32 MFMAs
+            return plain ? launch<256, 256, 4, 2, false, false>(a, w, c, M, N, K, s)
+                         : launch<256, 256, 4, 2, false, true, true>(a, w, c, M, N, K, s);
         case 2: ISO_DTL(256, 128, 4, 2);
         case 4: ISO_DTL(128, 256, 2, 4);
         case 5: ISO_DTL(256, 256, 2, 2);
@@ -623,7 +648,7 @@ hipError_t iso_launch_gemm_swiglu_bf16(const void *a, const void *w, void *act, 
     int v = variant & 7;
     if (v == 0) v = sk_wanted(M, 2 * F, K, sk) ? 6 : pick_variant(M, 2 * F);
     switch (v) {
-        case 1: return launch<256, 256, 4, 2, true, true>(a, w, act, M, 2 * F, K, s);
+        case 1: return launch<256, 256, 4, 2, true, true, true>(a, w, act, M, 2 * F, K, s);
         case 2: return launch<256, 128, 4, 2, true, true>(a, w, act, M, 2 * F, K, s);
         case 4: return launch<128, 256, 2, 4, true, true>(a, w, act, M, 2 * F, K, s);
         case 6: return (sk && sk->base) ? launch_sk<true>(a, w, act, M, 2 * F, K, sk, s) : hipErrorInvalidValue;

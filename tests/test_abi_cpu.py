@@ -112,15 +112,19 @@ def test_plan_chunk_count():
 
 
 def test_gemm_launch_plan_choices_and_invariants():
-    """Host logic that picks the projection kernel: stream-K only with enough k depth per team, its grid a whole
-    number of teams per XCD and never larger than the device, the team size a divisor of the tile rows."""
+    """Host logic that picks the projection kernel: stream-K only with enough k depth per team and only where whole
+    tiles would fill their rounds of the chip to less than 85 %, its grid a whole number of teams per XCD and never
+    larger than the device, the team size a divisor of the tile rows."""
     SK, T256, T128 = iso.ISO_GEMM_STREAMK, iso.ISO_GEMM_TILE_256, iso.ISO_GEMM_TILE_128
     # the projections of the 30B TP=4 chunk (M = 1024) and of the 70B TP=4 chunk (M = 4096) on 256 compute units
     assert iso.gemm_launch_plan(1024, 8960, 6656) == (SK, 4, 256)          # gate/up: 35 columns x 104 slices / 64 teams
     assert iso.gemm_launch_plan(1024, 6656, 1664)[0] == T128               # o_proj: only 10 slices per team
     assert iso.gemm_launch_plan(1024, 6656, 4480) == (SK, 4, 256)          # down: 28 slices per team
     assert iso.gemm_launch_plan(2048, 8192, 1024)[0] == T256               # 70B TP=8 o_proj: 16 slices per team
-    assert iso.gemm_launch_plan(4096, 8192, 7168) == (SK, 8, 256)
+    assert iso.gemm_launch_plan(4096, 8192, 7168) == (T256, 1, 512)       # 512 whole tiles: two full rounds, no stream-K
+    assert iso.gemm_launch_plan(4096, 14336, 8192) == (T256, 1, 896)      # 3.5 rounds of whole tiles fill 87.5 % of four
+    assert iso.gemm_launch_plan(4096, 2560, 8192) == (SK, 8, 256)         # 160 tiles: 62 % of one round
+    assert iso.gemm_launch_plan(3072, 8192, 4096) == (SK, 4, 256)         # 384 tiles: 75 % of two rounds
     assert iso.gemm_launch_plan(4096, 8192, 7168, num_cu=0) == (T256, 1, 512)   # no workspace: one tile per workgroup
     assert iso.gemm_launch_plan(300, 257 * 8, 1000)[0] in (iso.ISO_GEMM_STAGED, iso.ISO_GEMM_SIMPLE)   # K % 64 != 0
     assert iso.gemm_launch_plan(7, 12, 9)[0] == iso.ISO_GEMM_SIMPLE
@@ -136,6 +140,8 @@ def test_gemm_launch_plan_choices_and_invariants():
             assert 0 < grid <= cus and grid % (8 * team) == 0
             teams = grid // team
             assert (tiles_m // team) * tiles_n * nk // teams >= 20
+            rounds = -(-tiles_m * tiles_n // cus)
+            assert tiles_m * tiles_n * 100 < 85 * rounds * cus       # whole tiles would leave the chip idle
         elif kind == T256:
             assert grid == tiles_m * tiles_n and grid >= 128
         else:
