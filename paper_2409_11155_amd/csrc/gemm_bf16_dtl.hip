@@ -10,7 +10,8 @@
 //     32 consecutive rows then spread over all 64 banks (measured: 0 bank conflicts).
 //   * Workgroup tile BM x BN (up to 256 x 256), k slice 64, two LDS stages (a third one for W where the LDS allows,
 //     so that weight slices are requested two slices ahead); WM x WN wavefronts, each
-//     owning a (BM/WM) x (BN/WN) block of 32x32x16 MFMA tiles.  The 8-wave shapes put two waves on every
+//     owning a (BM/WM) x (BN/WN) block of MFMA tiles (32x32x16; the tile-per-workgroup launch of the 256x256 tile
+//     issues 16x16x32 instead, which does more arithmetic per watt: this chip runs into its power limit first).  The 8-wave shapes put two waves on every
 //     SIMD, which is what keeps the matrix pipe fed: a single wave cannot issue MFMAs back to back without
 //     gaps (a register-only MFMA loop reaches ~82 % of peak with one wave per SIMD, ~99 % with two).
 //   * Operand fragments are double-buffered in registers, and the slice hand-over (wait for the next
@@ -167,26 +168,37 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
     // Accumulators: one f32x16 per 32x32 block of the wave tile.  M16 keeps the four 16x16 sub-blocks (si, sj) of a
     // block in registers 4 * (2 si + sj) .. + 3 of that vector.
     f32x16_t acc[TM][TN];
-    bf16x8_t af[2][FM], wf[2][FN];
-    auto read_frags2 = [&](const unsigned char *abase, const unsigned char *wbase, int buf, int ks) {
+    // A k-step is worked off in HS phases over the W fragments (M16: two halves of four, so that the double-buffered
+    // fragments take 64 registers instead of 96; 32x32x16: one).  Phase p = (k-step p / HS, half p % HS) reads its W
+    // fragments into wf[p & 1] and, in the first half of a k-step, the A fragments into af[k-step & 1].
+    constexpr int HS = M16 ? 2 : 1, FNH = FN / HS, NPH = NKS * HS;
+    static_assert(!M16 || PIPE, "the 16x16x32 path exists for the interleaved main loop");
+    static_assert(NKS % 2 == 0 && FN % HS == 0, "buffers alternate cleanly across slices");
+    bf16x8_t af[2][FM], wf[2][FNH];
+    auto read_phase = [&](const unsigned char *abase, const unsigned char *wbase, int ph) {
+        const int ks = ph / HS, h = ph % HS;
         const int chunk_off = ((ks * (KSTEP / 8) + fgrp) ^ f_sw) << 4;
-        const unsigned char *ap = abase + a_row0 + chunk_off, *wp = wbase + w_row0 + chunk_off;
+        if (h == 0) {
+            const unsigned char *ap = abase + a_row0 + chunk_off;
 #pragma unroll
-        for (int i = 0; i < FM; ++i) af[buf][i] = *reinterpret_cast<const bf16x8_t *>(ap + i * MR * ROW_BYTES);
+            for (int i = 0; i < FM; ++i) af[ks & 1][i] = *reinterpret_cast<const bf16x8_t *>(ap + i * MR * ROW_BYTES);
+        }
+        const unsigned char *wp = wbase + w_row0 + chunk_off + h * FNH * MR * ROW_BYTES;
 #pragma unroll
-        for (int j = 0; j < FN; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8_t *>(wp + j * MR * ROW_BYTES);
+        for (int j = 0; j < FNH; ++j) wf[ph & 1][j] = *reinterpret_cast<const bf16x8_t *>(wp + j * MR * ROW_BYTES);
     };
-    auto read_frags = [&](const unsigned char *base, int buf, int ks) { read_frags2(base, base, buf, ks); };
-    auto mfma_step = [&](int buf) {
+    auto mfma_phase = [&](int ph) {
+        const int ks = ph / HS, h = ph % HS;
         if constexpr (M16) {
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j) {
+                for (int jj = 0; jj < FNH; ++jj) {
+                    const int j = h * FNH + jj;
                     f32x16_t &blk = acc[i / 2][j / 2];
                     const int q = 4 * (2 * (i & 1) + (j & 1));
                     f32x4_t sub = {blk[q], blk[q + 1], blk[q + 2], blk[q + 3]};
-                    sub = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[buf][i], wf[buf][j], sub, 0, 0, 0);
+                    sub = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks & 1][i], wf[ph & 1][jj], sub, 0, 0, 0);
                     blk[q] = sub[0]; blk[q + 1] = sub[1]; blk[q + 2] = sub[2]; blk[q + 3] = sub[3];
                 }
         } else {
@@ -194,9 +206,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], wf[buf][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], wf[ph & 1][j], acc[i][j], 0, 0, 0);
         }
     };
+    // k-step forms for the plain loop (one phase per k-step there)
+    auto read_frags = [&](const unsigned char *base, int buf, int ks) { (void)buf; read_phase(base, base, ks); };
+    auto mfma_step = [&](int buf) { mfma_phase(buf); };
     // Row and column, inside its 32x32 block, of accumulator register r of this lane.
     auto blk_row = [&](int r) { return M16 ? 16 * (r / 8) + 4 * fgrp + (r % 4) : 8 * (r / 4) + 4 * fgrp + (r % 4); };
     auto blk_col = [&](int r) { return M16 ? 16 * ((r / 4) & 1) + frow : frow; };
@@ -242,7 +257,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
             // hand-over step, the direct-to-LDS loads two slices ahead) are slotted between the MFMAs, one
             // memory instruction per MFMA, so a wave's memory issue runs in the shadow of its own matrix
             // instructions instead of leaving the matrix pipe idle.
-            constexpr int NMFMA = FM * FN, NREAD = FM + FN, NLOAD = A_LOADS + W_LOADS;
+            constexpr int NMFMA = FM * FNH, NREAD = FM + FNH, NLOAD = A_LOADS + W_LOADS;   // per phase (reads: at most)
             auto weave = [&](bool with_loads) {
 #pragma unroll
                 for (int i = 0; i < NREAD; ++i) {
@@ -269,9 +284,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                 const int wnx = wst + 1 == WS ? 0 : wst + 1;
                 const unsigned char *abase = lds + (kt & 1) * A_STRIDE, *wbase = lds + wst * W_STRIDE;
 #pragma unroll
-                for (int ks = 0; ks < NKS - 1; ++ks) {
-                    read_frags2(abase, wbase, (ks + 1) & 1, ks + 1);
-                    mfma_step(ks & 1);
+                for (int ph = 0; ph < NPH - 1; ++ph) {
+                    read_phase(abase, wbase, ph + 1);
+                    mfma_phase(ph);
                     weave(false);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -282,14 +297,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
                     // wait above is the fence this hand-over needs, and the memory clobber keeps LDS accesses in place.
                     if (W3) asm volatile("s_barrier" ::: "memory");
                     else __syncthreads();
-                    read_frags2(lds + ((kt + 1) & 1) * A_STRIDE, lds + wnx * W_STRIDE, 0, 0);
+                    read_phase(lds + ((kt + 1) & 1) * A_STRIDE, lds + wnx * W_STRIDE, 0);
                     if (more) {
                         issue_a(kt & 1, (kb + kt + 2) * BK);
                         if (W3) issue_w(wst, (kb + min(kt + 3, n - 1)) * BK);
                         else issue_w(kt & 1, (kb + kt + 2) * BK);
                     }
                 }
-                mfma_step((NKS - 1) & 1);
+                mfma_phase(NPH - 1);
                 if (handover) weave(more);
                 __builtin_amdgcn_sched_barrier(0);
                 wst = wnx;
@@ -301,7 +316,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
     };
 
     // ---- epilogue.  Accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its
-    //      32x32 tile.  Each wave parks its tile as bf16 in its own LDS region, then streams it out in
+    //      32x32 tile (16x16x32 path: row 16*(r/8) + 4*(l/16) + r%4, column 16*((r/4)%2) + l%16).  Each wave parks its tile as bf16 in its own LDS region, then streams it out in
     //      16-byte pieces so that every store instruction covers whole 256-byte row segments.
     auto store_tile = [&]() {
         __syncthreads();                         // every wave is done reading operand tiles
@@ -614,8 +629,10 @@ void iso_gemm_bf16_dtl_plan(int M, int N, int K, int num_wg, int *kind, int *tea
     *grid = G;
 }
 
-// variant: 0 = pick by shape; 1 = 256x256 8 waves, 2 = 256x128 8 waves, 3 = 128x128 4 waves, 4 = 128x256 8 waves,
-//          5 = 256x256 4 waves, 6 = 256x256 stream-K; +8 selects the plain (non-interleaved) main loop.
+// variant: 0 = pick by shape; 1 = 256x256 8 waves (16x16x32 MFMAs: measured 6-8 % ahead of 32x32x16 on the launches
+//          that fill the chip, 2-6 % behind on the smaller tiles and in the stream-K launch, which keep 32x32x16),
+//          2 = 256x128 8 waves, 3 = 128x128 4 waves, 4 = 128x256 8 waves, 5 = 256x256 4 waves, 6 = 256x256 stream-K;
+//          +8 selects the plain (non-interleaved) main loop.
 // sk may be null: then the stream-K kernel is not considered (variant 6 is an error).
 hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M, int N, int K, int variant,
                                     iso_sk_ws *sk, hipStream_t s) {
