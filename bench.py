@@ -1,11 +1,16 @@
 """Benchmark of the ISO layer-shard prefill on one MI355X.
 
-A step is one pass of the whole hot path -- one decoder-layer shard over one synthetic prompt, cut into two
-chunks, chunk 0 on stream 0 and chunk 1 on stream 1, with the device-to-host copy standing in for the
-all-reduce at both communication points -- through libiso's C ABI.  Inputs are resident in HBM before the
-timed region.  Prints ONE JSON line.
+A step is one pass of the whole hot path over one synthetic prompt: every layer of the workload's stack, the prompt
+cut into two chunks, chunk 0 on stream 0 and chunk 1 on stream 1, with the device-to-host copy standing in for the
+all-reduce at both communication points of every layer -- through libiso's C ABI.  Inputs are resident in HBM before
+the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--split S] [--no-cpu-baseline]
+The default workload is the largest configuration one GPU holds: the 80-layer 70B TP=8 stack over a 16k prompt
+(`70b_tp8_16k_stack`).  The record of the 2k-prompt 30B TP=4 layer (`30b_tp4_2k`, with the finer-cut, segmented-GEMM
+and FP8 variants that are cheap there) rides along as a side object.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--split S] [--layers L]
+                    [--no-cpu-baseline] [--no-side] [--headline-only]
 """
 from __future__ import annotations
 
@@ -14,6 +19,7 @@ import json
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -22,6 +28,10 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
+DEFAULT_WORKLOAD = "70b_tp8_16k_stack"
+SIDE_WORKLOAD = "30b_tp4_2k"
+METRIC = "prefill tokens/s per layer shard (ISO vs unsplit) + attn/GEMM % MFMA peak"
+MAX_TIMED_LAUNCHES = 65000         # the library keeps at most 65536 timed launches per pass
 
 
 def parse_args():
@@ -29,17 +39,18 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="30b_tp4_2k")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--split", type=int, default=-1, help="split point (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-side", action="store_true", help="leave out the side record of the 30b_tp4_2k layer")
     ap.add_argument("--headline-only", action="store_true",
                     help="time only the ISO-scheduled steps of the headline (every launch of the run then has the "
                          "headline's shapes and schedule: the form to run under a profiler)")
     ap.add_argument("--flags", type=int, default=0, help="kernel-choice flags (ISO_FLAG_*), for ablations")
     ap.add_argument("--layers", type=int, default=0, help="layers of a stack workload (default: the workload's)")
-    ap.add_argument("--distinct-layers", type=int, default=4,
-                    help="a stack draws this many distinct weight sets on the host and gives every layer its own "
-                         "device copy of one of them (layer l uses set l %% D)")
+    ap.add_argument("--distinct-layers", type=int, default=0,
+                    help="draw only this many distinct weight sets for a stack and give layer l its own device copy of "
+                         "set l %% D (default 0: one seed per layer, every layer its own draw)")
     return ap.parse_args()
 
 
@@ -48,33 +59,30 @@ def note(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def main() -> int:
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding across GPUs); "
-              "--gpus must be 1", file=sys.stderr)
-        return 2
-
-    import paper_2409_11155_amd as iso      # first: binds libiso to the HIP runtime it was built against
-    import iso_inputs
-
-    if iso.device_count() < 1:
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    wl = iso_inputs.WORKLOADS[args.workload]
-    T = wl.seq
-    dt = wl.dtype
-    split = wl.split if args.split < 0 else args.split
-    L = args.layers if args.layers > 0 else wl.n_layers
-    note(f"workload {args.workload}: T={T} layers={L} steps={args.steps} warmup={args.warmup}; drawing inputs")
+def measure(iso, iso_inputs, args, name, L, K, W, split_arg, full, cpu_baseline):
+    """All timings of one workload.  full=True: every variant at K steps (cheap single layers); full=False: the
+    headline, the schedules it is compared with and one per-kernel pass at K steps, every other variant at <= 3."""
+    wl = iso_inputs.WORKLOADS[name]
+    T, dt = wl.seq, wl.dtype
+    split = wl.split if split_arg < 0 else split_arg
+    Ks, Wsd = (K, W) if full else (min(K, 3), min(W, 1))       # steps / warm-up of the side variants
+    note(f"workload {name}: T={T} layers={L} steps={K} warmup={W}; drawing inputs")
+    t_draw = time.perf_counter()
     x_cpu, w_cpu = iso_inputs.make_workload_inputs(wl, seed=0)
-    note("uploading weights")
+    n_sets = L if args.distinct_layers <= 0 else min(L, args.distinct_layers)
     if L == 1:
         layers = [iso.upload_weights(w_cpu, dt)]
-    else:   # every layer owns its device buffers; the host draws only a few distinct sets (see --distinct-layers)
-        host_sets = [w_cpu] + [iso_inputs.make_workload_inputs(wl, seed=0, layer=l)[1]
-                               for l in range(1, min(L, max(1, args.distinct_layers)))]
-        layers = [iso.upload_weights(host_sets[l % len(host_sets)], dt) for l in range(L)]
+    else:
+        # one seed per layer (layer l: seed l); the draws run on a few host threads, each layer is uploaded as soon
+        # as it is drawn and its host copy dropped
+        def draw(l):
+            return w_cpu if l == 0 else iso_inputs.make_workload_inputs_layer(wl, seed=0, layer=l)
+        sets = []
+        with ThreadPoolExecutor(8) as ex:
+            for w in ex.map(draw, range(n_sets)):
+                sets.append(w if n_sets < L else iso.upload_weights(w, dt))
+        layers = sets if n_sets == L else [iso.upload_weights(sets[l % n_sets], dt) for l in range(L)]
+    note(f"inputs drawn and uploaded in {time.perf_counter() - t_draw:.1f} s ({n_sets} distinct weight sets)")
     x0 = iso.DeviceArray.from_numpy(x_cpu, dt)
     x = x0.clone()
     kc = iso.DeviceArray((L, T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=0)
@@ -82,7 +90,6 @@ def main() -> int:
     cfg = iso.make_cfg(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, T)
     ctx = iso.Context(cfg)
     ctx.set_flags(args.flags)
-    K, W = args.steps, args.warmup
 
     def run(n, sp, comm, sched):
         for _ in range(n):
@@ -91,61 +98,130 @@ def main() -> int:
             else:
                 ctx.stack_prefill(layers, x, kc, vc, T, sp, comm, sched)
 
-    def timed(sp, comm, sched):
-        """W warm-up steps, then exactly K steps between two full synchronisations; ms per step."""
-        note(f"timing split={sp} comm={comm} sched={sched}")
+    def timed(sp, comm, sched, k=None, w=None):
+        """w warm-up steps, then exactly k steps between two full synchronisations; ms per step."""
+        k = K if k is None else k
+        w = W if w is None else w
+        note(f"timing split={sp} comm={comm} sched={sched} steps={k}")
         x.copy_from(x0)
-        run(W, sp, comm, sched)
+        run(w, sp, comm, sched)
         ctx.sync()
         iso.device_sync()
         t0 = time.perf_counter()
-        run(K, sp, comm, sched)
+        run(k, sp, comm, sched)
         ctx.sync()
         iso.device_sync()
-        return (time.perf_counter() - t0) * 1e3 / K
+        return (time.perf_counter() - t0) * 1e3 / k
 
-    D2H, NONE = iso.ISO_COMM_D2H, iso.ISO_COMM_NONE
-    OVL, SER = iso.ISO_SCHED_OVERLAP, iso.ISO_SCHED_SERIAL
+    D2H, NONE, INT8 = iso.ISO_COMM_D2H, iso.ISO_COMM_NONE, iso.ISO_COMM_D2H_INT8
+    OVL, SER, PCS = iso.ISO_SCHED_OVERLAP, iso.ISO_SCHED_SERIAL, iso.ISO_SCHED_STREAM_PER_CHUNK
+    launches_per_step = 24 * L
 
-    def headline_only(t_iso_ms):
-        """Reduced record: the timed ISO steps plus one per-kernel timing pass in the same schedule."""
+    def kinds(sp, comm, sched, steps):
+        """Per-kernel durations from HIP events recorded around every launch in the launch's own stream."""
         x.copy_from(x0)
-        run(2, split, D2H, OVL)
+        run(1 if not full else 2, sp, comm, sched)
         ctx.sync()
         ctx.timing_enable(True)
-        steps = max(1, min(K, 20, 8000 // (24 * L)))
-        run(steps, split, D2H, OVL)
-        kd = ctx.timing_read()
+        run(steps, sp, comm, sched)
+        out = ctx.timing_read()
         ctx.timing_enable(False)
-        ms, n = kd["gemm_gate_up"]
-        flops = 4.0 * wl.hidden * wl.ffn * L * T / (n / steps)
-        avg_ms = ms / n
-        bf = wl.dtype == "bf16"
-        pk = MFMA_BF16_PEAK_TFLOPS if bf else FP32_VECTOR_PEAK_TFLOPS
-        ach = flops / (avg_ms * 1e-3) / 1e12
-        print(json.dumps({
-            "metric": "prefill tokens/s per layer shard (ISO vs unsplit) + attn/GEMM % MFMA peak",
-            "value": T / (t_iso_ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
-            "ms_per_step": t_iso_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": wl.dtype, "data": "synthetic", "config": {"workload": wl.name, "seq": T, "split": split, "layers": L},
-            "headline_only": True,
-            "roofline": {"bound": "mfma" if bf else "alu", "achieved": ach, "peak": pk, "unit": "TFLOP/s",
-                         "frac": ach / pk, "traffic": None, "avg_launch_ms": avg_ms, "flops_per_launch": flops,
-                         "launches": n},
-            "kernel_ms_per_step": {k: v[0] / steps for k, v in kd.items() if v[1]},
-            "kernel_launches_per_step": {k: v[1] // steps for k, v in kd.items() if v[1]}}))
-        ctx.close()
-        return 0
+        return {k: (ms / steps, n // steps) for k, (ms, n) in out.items()}
+
+    H, F, d, nq, nkv = wl.hidden, wl.ffn, wl.head_dim, wl.n_q_heads, wl.n_kv_heads
+    bf16 = wl.dtype == "bf16"
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    gemm_flops_tok = {"gemm_qkv": 2.0 * H * wl.n_qkv * L, "gemm_o": 2.0 * nq * d * H * L,
+                      "gemm_gate_up": 4.0 * H * F * L, "gemm_down": 2.0 * F * H * L}      # per token, all layers
+    two = 0 < split < T
+    attn_flops = L * ((wl.attn_flops(0, split) + wl.attn_flops(split, T - split)) if two else wl.attn_flops(0, T))
+    e = 2 if bf16 else 4
+    # algorithmic bytes per token of the bandwidth-bound kernels (each byte once)
+    bytes_tok = {"rmsnorm": 2 * H * e, "resid_norm": 4 * H * e * (2 * L - 1), "residual": 3 * H * e,
+                 "rope_kv": (2 * (nq + nkv) * d + 2 * nkv * d) * e * L, "swiglu": 3 * F * e * L}
+
+    def per_kernel(kd):
+        out = {}
+        for kname, fl in gemm_flops_tok.items():
+            ms, n = kd[kname]
+            if n:
+                tf = fl * T / (ms * 1e-3) / 1e12
+                out[kname] = {"ms": ms, "launches": n, "tflops": tf, "frac_of_peak": tf / peak}
+        ms, n = kd["attn"]
+        if n:
+            tf = attn_flops / (ms * 1e-3) / 1e12
+            out["attn"] = {"ms": ms, "launches": n, "tflops": tf, "frac_of_peak": tf / peak}
+        for kname, b in bytes_tok.items():
+            ms, n = kd[kname]
+            if n:
+                out[kname] = {"ms": ms, "launches": n, "gbs": b * T / (ms * 1e-3) / 1e9,
+                              "frac_of_hbm_peak": b * T / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        ms, n = kd["comm"]
+        if n:
+            out["comm"] = {"ms": ms, "launches": n, "gbs": 2.0 * L * T * H * e / (ms * 1e-3) / 1e9}
+        return out
+
+    def roofline_of(k_iso, k_alone):
+        """Dominant kernel: the gate/up projection (SwiGLU in its epilogue for bf16); one launch per chunk and layer,
+        algorithmic work of a launch = 2 * Tc * 2F * H flops, averaged over the chunks."""
+        dom = "gemm_gate_up"
+        dom_ms, dom_n = k_iso[dom]
+        flops_per_launch = gemm_flops_tok[dom] * T / dom_n
+        ach = flops_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
+        traffic = algorithmic = None
+        tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+        if os.path.exists(tpath):
+            try:
+                with open(tpath) as f:
+                    ent = json.load(f).get(name, {})
+                traffic, algorithmic = ent.get("gate_up_bytes_per_launch"), ent.get("algorithmic_bytes_per_launch")
+            except Exception:
+                traffic = None
+        r = {"bound": "mfma" if bf16 else "alu",
+             "kernel": ("gemm_bf16_dtl_kernel<.., SWIGLU=true> (gate/up projection + SwiGLU)" if bf16
+                        else "gemm_simple_kernel<float> (gate/up projection)"),
+             "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
+             "algorithmic_bytes_per_launch": algorithmic,
+             "avg_launch_ms": dom_ms / dom_n, "flops_per_launch": flops_per_launch,
+             "launch_shape": {"M": T * L // dom_n, "N": 2 * F, "K": H, "launches_per_step": dom_n},
+             "measured": "HIP events around each launch, in its own stream, during ISO-scheduled steps"}
+        if k_alone is not None:
+            dom_ms_alone, _ = k_alone[dom]
+            ach_alone = flops_per_launch / (dom_ms_alone / dom_n * 1e-3) / 1e12
+            r.update({"achieved_alone": ach_alone, "frac_alone": ach_alone / peak,
+                      "avg_launch_ms_alone": dom_ms_alone / dom_n,
+                      "all_gemms_tflops_alone": sum(gemm_flops_tok.values()) * T /
+                                                (sum(k_alone[n][0] for n in gemm_flops_tok) * 1e-3) / 1e12})
+        return r
+
+    config = {"workload": wl.name, "hidden": H, "n_q_heads": nq, "n_kv_heads": nkv, "head_dim": d, "ffn": F,
+              "seq": T, "split": split, "layers": L, "distinct_weight_sets": n_sets,
+              "weights": "one seed per layer" if n_sets == L else f"{n_sets} draws, layer l uses set l % {n_sets}",
+              "comm": "d2h copy of the bf16 [Tc,hidden] partial at both points of every layer",
+              "schedule": "two streams, chunk per stream, no join between layers"}
+    layer_flops = wl.gemm_flops() * L + attn_flops
+    ksteps = max(1, min(K, 20, MAX_TIMED_LAUNCHES // launches_per_step))
+
     t_iso = timed(split, D2H, OVL)                 # the headline: ISO schedule with the copy stand-in
-    ho = args.headline_only
-    if ho:
-        return headline_only(t_iso)
+    base = {"metric": METRIC, "value": T / (t_iso * 1e-3),
+            "unit": "tokens/s" if L == 1 else f"tokens/s through {L} layers", "n_gpus": 1, "steps": K, "warmup": W,
+            "ms_per_step": t_iso, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": wl.dtype, "data": "synthetic", "config": config,
+            "tflops": layer_flops / (t_iso * 1e-3) / 1e12, "layer_tokens_per_s": T * L / (t_iso * 1e-3)}
+    if args.headline_only:
+        k_iso = kinds(split, D2H, OVL, ksteps)
+        base.update({"headline_only": True, "roofline": roofline_of(k_iso, None),
+                     "kernel_ms_per_step": {k: v[0] for k, v in k_iso.items() if v[1]},
+                     "kernel_launches_per_step": {k: v[1] for k, v in k_iso.items() if v[1]}})
+        ctx.close()
+        return base
+
     # the same ISO step timed one at a time (a synchronisation after every step): median and minimum
     x.copy_from(x0)
-    run(W, split, D2H, OVL)
+    run(Wsd, split, D2H, OVL)
     ctx.sync()
     per_step = []
-    for _ in range(K):
+    for _ in range(Ks):
         iso.device_sync()
         t0 = time.perf_counter()
         run(1, split, D2H, OVL)
@@ -153,43 +229,43 @@ def main() -> int:
         per_step.append((time.perf_counter() - t0) * 1e3)
     per_step.sort()
     t_iso_single = {"median_ms": per_step[len(per_step) // 2], "min_ms": per_step[0], "max_ms": per_step[-1],
-                    "note": "one step per synchronisation; the headline times K steps back to back"}
-    t_serial = timed(split, D2H, SER)              # same chunks, one stream: compute + copies back to back
-    t_unsplit = timed(0, D2H, SER)                 # the pipeline ISO is compared with
-    t_iso_nocomm = timed(split, NONE, OVL)
-    t_unsplit_nocomm = timed(0, NONE, SER)
+                    "steps": Ks, "note": "one step per synchronisation; the headline times K steps back to back"}
+    w_cmp = W if full else min(W, 1)               # long steps need no long warm-up
+    t_serial = timed(split, D2H, SER, K, w_cmp)    # same chunks, one stream: compute + copies back to back
+    t_unsplit = timed(0, D2H, SER, K, w_cmp)       # the pipeline ISO is compared with
+    t_iso_nocomm = timed(split, NONE, OVL, K, w_cmp)
+    t_unsplit_nocomm = timed(0, NONE, SER, K, w_cmp)
     # the paper's remedy when communication dominates (Section 3.2): int8 payload, half the bytes
-    INT8 = iso.ISO_COMM_D2H_INT8
-    t_iso_int8 = timed(split, INT8, OVL)
-    t_unsplit_int8 = timed(0, INT8, SER)
+    t_iso_int8 = timed(split, INT8, OVL, Ks, Wsd)
+    t_unsplit_int8 = timed(0, INT8, SER, Ks, Wsd)
 
     # Section 6: finer cuts than two chunks.  Cost-balanced cut points from the library's planner; chunks on the two
     # streams in turn, or one stream per chunk with the attention blocks chained in chunk order.
     def timed_chunks(bounds, comm, sched):
-        note(f"timing {len(bounds) + 1} chunks comm={comm} sched={sched}")
+        note(f"timing {len(bounds) + 1} chunks comm={comm} sched={sched} steps={Ks}")
         def go(n):
             for _ in range(n):
                 ctx.stack_prefill_chunks(layers, x, kc, vc, T, bounds, comm, sched)
         x.copy_from(x0)
-        go(W)
+        go(Wsd)
         ctx.sync()
         iso.device_sync()
         t0 = time.perf_counter()
-        go(K)
+        go(Ks)
         ctx.sync()
         iso.device_sync()
-        return (time.perf_counter() - t0) * 1e3 / K
+        return (time.perf_counter() - t0) * 1e3 / Ks
 
     finer = {}
-    PCS = iso.ISO_SCHED_STREAM_PER_CHUNK
-    for n_chunks in (2, 3, 4, 6, 8):
+    for n_chunks in ((2, 3, 4, 6, 8) if full else (4, 8)):
         if T < 256 * n_chunks:
             continue
         bounds = iso.plan_split(cfg, T, n_chunks)
         entry = {"bounds": bounds}
-        for sname, sched in (("two_streams", OVL), ("stream_per_chunk", PCS)):
-            entry[sname] = {"t_ms": timed_chunks(bounds, D2H, sched), "t_int8_ms": timed_chunks(bounds, INT8, sched),
-                            "t_nocomm_ms": timed_chunks(bounds, NONE, sched)}
+        for sname, sched in ((("two_streams", OVL), ("stream_per_chunk", PCS)) if full else (("stream_per_chunk", PCS),)):
+            entry[sname] = {"t_ms": timed_chunks(bounds, D2H, sched), "t_int8_ms": timed_chunks(bounds, INT8, sched)}
+            if full:
+                entry[sname]["t_nocomm_ms"] = timed_chunks(bounds, NONE, sched)
         finer[str(n_chunks)] = entry
 
     # Section 3.2, computation-dominated case: (a) how much a kernel slows down while the copy engine runs beside it
@@ -216,133 +292,64 @@ def main() -> int:
             out[label + "_ms"] = ms
         out["slowdown"] = out["beside_copies_ms"] / out["alone_ms"] - 1.0
         out["shape"] = {"M": M, "N": N, "K": Kd}
+        c.free()
         return out
 
     sink_buf = iso.PinnedArray((64 << 20,), "bf16")      # 128 MiB of pinned memory for the copies of (a)
     seg = {"gate_up_gemm": gate_up_alone_vs_beside_copies(), "t_iso_ms": {}, "t_iso_nocomm_ms": {}}
     sink_buf.free()
-    for n_seg in (1, 2, 4):
+    for n_seg in ((1, 2, 4) if full else (2,)):
         ctx.set_gemm_segments(n_seg)
-        seg["t_iso_ms"][str(n_seg)] = timed(split, D2H, OVL)
-        seg["t_iso_nocomm_ms"][str(n_seg)] = timed(split, NONE, OVL)
+        seg["t_iso_ms"][str(n_seg)] = timed(split, D2H, OVL, Ks, Wsd)
+        seg["t_iso_nocomm_ms"][str(n_seg)] = timed(split, NONE, OVL, Ks, Wsd)
     ctx.set_gemm_segments(1)
 
     # FP8 projections (Section 4.1: the paper's matrix products run in 8 bits): same schedule, the four GEMMs on the
     # FP8 matrix cores with per-row scales, activations quantised on the fly
     fp8 = None
-    if wl.dtype == "bf16":
+    if bf16:
         bf16_layers = layers
         layers = [ctx.add_fp8_weights(w) for w in bf16_layers]
         ctx.set_flags(args.flags | iso.ISO_FLAG_FP8_GEMM)
-        fp8 = {"t_iso_ms": timed(split, D2H, OVL), "t_iso_int8_ms": timed(split, INT8, OVL),
-               "t_iso_nocomm_ms": timed(split, NONE, OVL), "t_unsplit_nocomm_ms": timed(0, NONE, SER)}
+        fp8 = {"t_iso_ms": timed(split, D2H, OVL, Ks, Wsd), "t_iso_int8_ms": timed(split, INT8, OVL, Ks, Wsd),
+               "t_iso_nocomm_ms": timed(split, NONE, OVL, Ks, Wsd), "t_unsplit_nocomm_ms": timed(0, NONE, SER, Ks, Wsd)}
         if T >= 768:       # all three remedies of the paper together: 8-bit products, int8 payload, finer cuts
-            b3 = iso.plan_split(cfg, T, 3)
-            fp8["t_iso_int8_3_chunks_ms"] = timed_chunks(b3, INT8, iso.ISO_SCHED_STREAM_PER_CHUNK)
-            fp8["bounds_3_chunks"] = b3
+            b3 = iso.plan_split(cfg, T, 3 if full else 4)
+            fp8["t_iso_int8_finer_chunks_ms"] = timed_chunks(b3, INT8, PCS)
+            fp8["bounds_finer_chunks"] = b3
         x.copy_from(x0)
-        run(2, split, NONE, SER)
+        run(1, split, NONE, SER)
         ctx.sync()
         ctx.timing_enable(True)
-        f8steps = max(1, min(10, 8000 // (28 * L)))
+        f8steps = max(1, min(Ks, 10, MAX_TIMED_LAUNCHES // (28 * L)))
         run(f8steps, split, NONE, SER)
         kd = ctx.timing_read()
         ctx.timing_enable(False)
-        gemm_ms = {k: kd[k][0] / f8steps for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down")}
-        fl = {"gemm_qkv": 2.0 * wl.hidden * wl.n_qkv, "gemm_o": 2.0 * wl.n_q_heads * wl.head_dim * wl.hidden,
-              "gemm_gate_up": 4.0 * wl.hidden * wl.ffn, "gemm_down": 2.0 * wl.ffn * wl.hidden}
-        fp8["gemm_tflops_alone"] = {k: fl[k] * T * L / (gemm_ms[k] * 1e-3) / 1e12 for k in gemm_ms}
+        gemm_ms = {k: kd[k][0] / f8steps for k in gemm_flops_tok}
+        fp8["gemm_tflops_alone"] = {k: gemm_flops_tok[k] * T / (gemm_ms[k] * 1e-3) / 1e12 for k in gemm_ms}
         fp8["quantiser_ms_per_step"] = kd["quant"][0] / f8steps
         fp8["gate_up_frac_of_fp8_peak"] = fp8["gemm_tflops_alone"]["gemm_gate_up"] / 5000.0
+        fp8["steps"] = Ks
         fp8["note"] = ("E4M3 operands, one fp32 scale per token row / output channel, fp32 accumulation; parity bound "
                        "is wider than bf16 (see tests/test_gpu_fp8.py); not the headline")
         ctx.set_flags(args.flags)
         layers = bf16_layers
 
     # ---- per-kernel durations, measured live with HIP events in the launch streams ----------------
-    def kinds(sp, comm, sched, steps):
-        x.copy_from(x0)
-        run(2, sp, comm, sched)
-        ctx.sync()
-        ctx.timing_enable(True)
-        run(steps, sp, comm, sched)
-        out = ctx.timing_read()
-        ctx.timing_enable(False)
-        return {k: (ms / steps, n // steps) for k, (ms, n) in out.items()}
-
-    ksteps = max(1, min(K, 20, 8000 // (24 * L)))    # the library keeps at most 8192 timed launches per pass
+    note(f"per-kernel timing passes ({ksteps} steps in the ISO schedule)")
     k_iso = kinds(split, D2H, OVL, ksteps)           # as scheduled in the timed ISO steps
     k_alone = kinds(split, NONE, SER, ksteps)        # same launches, one stream, nothing concurrent
-    k_comm = kinds(split, D2H, SER, ksteps)
-    k_int8 = kinds(split, INT8, SER, ksteps)
-
-    H, F, d, nq = wl.hidden, wl.ffn, wl.head_dim, wl.n_q_heads
-    gemm_flops_tok = {"gemm_qkv": 2.0 * H * wl.n_qkv * L, "gemm_o": 2.0 * nq * d * H * L,
-                      "gemm_gate_up": 4.0 * H * F * L, "gemm_down": 2.0 * F * H * L}      # per token, all layers
-    two = 0 < split < T
-    attn_flops = L * ((wl.attn_flops(0, split) + wl.attn_flops(split, T - split)) if two else wl.attn_flops(0, T))
-    e = 2 if wl.dtype == "bf16" else 4
-    nkv = wl.n_kv_heads
-    bytes_tok = {"rmsnorm": 2 * H * e, "resid_norm": 4 * H * e * (2 * L - 1), "residual": 3 * H * e,
-                 "rope_kv": (2 * (nq + nkv) * d + 2 * nkv * d) * e * L, "swiglu": 3 * F * e * L}
-
-    def per_kernel(kd):
-        out = {}
-        for name, fl in gemm_flops_tok.items():
-            ms, n = kd[name]
-            if n:
-                tf = fl * T / (ms * 1e-3) / 1e12
-                out[name] = {"ms": ms, "launches": n, "tflops": tf, "frac_of_peak": tf / peak}
-        ms, n = kd["attn"]
-        if n:
-            tf = attn_flops / (ms * 1e-3) / 1e12
-            out["attn"] = {"ms": ms, "launches": n, "tflops": tf, "frac_of_peak": tf / peak}
-        for name, b in bytes_tok.items():
-            ms, n = kd[name]
-            if n:
-                out[name] = {"ms": ms, "launches": n, "gbs": b * T / (ms * 1e-3) / 1e9}
-        ms, n = kd["comm"]
-        if n:
-            out["comm"] = {"ms": ms, "launches": n, "gbs": 2.0 * L * T * H * e / (ms * 1e-3) / 1e9}
-        return out
-
-    bf16 = wl.dtype == "bf16"
-    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    k_comm = kinds(split, D2H, SER, min(ksteps, Ks))
+    k_int8 = kinds(split, INT8, SER, min(ksteps, Ks))
     pk_iso, pk_alone = per_kernel(k_iso), per_kernel(k_alone)
-    gemm_names = list(gemm_flops_tok)
-
-    # ---- roofline of the dominant kernel: the gate/up projection (SwiGLU in its epilogue for bf16) -------
-    # one launch per chunk; algorithmic work of a launch = 2 * Tc * 2F * H flops, averaged over the chunks
-    dom = "gemm_gate_up"
-    dom_ms, dom_n = k_iso[dom]
-    dom_ms_alone, _ = k_alone[dom]
-    flops_per_launch = gemm_flops_tok[dom] * T / dom_n
-    ach = flops_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
-    ach_alone = flops_per_launch / (dom_ms_alone / dom_n * 1e-3) / 1e12
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            with open(tpath) as f:
-                traffic = json.load(f).get(args.workload, {}).get("gate_up_bytes_per_launch")
-        except Exception:
-            traffic = None
-    roofline = {"bound": "mfma" if bf16 else "alu",
-                "kernel": ("gemm_bf16_dtl_kernel<.., SWIGLU=true> (gate/up projection + SwiGLU)" if bf16
-                           else "gemm_simple_kernel<float> (gate/up projection)"),
-                "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
-                "avg_launch_ms": dom_ms / dom_n, "flops_per_launch": flops_per_launch,
-                "launch_shape": {"M": T * L // dom_n, "N": 2 * F, "K": H, "launches_per_step": dom_n},
-                "measured": "HIP events around each launch, in its own stream, during ISO-scheduled steps",
-                "achieved_alone": ach_alone, "frac_alone": ach_alone / peak,
-                "avg_launch_ms_alone": dom_ms_alone / dom_n,
-                "all_gemms_tflops_alone": sum(gemm_flops_tok.values()) * T /
-                                          (sum(k_alone[n][0] for n in gemm_names) * 1e-3) / 1e12,
-                "attention_tflops_alone": pk_alone.get("attn", {}).get("tflops")}
+    roofline = roofline_of(k_iso, k_alone)
+    roofline["attention_tflops_alone"] = pk_alone.get("attn", {}).get("tflops")
 
     sum_x = k_comm["comm"][0]                                   # all copies of a step, back to back
     sum_c = t_serial - sum_x if t_serial > sum_x else sum(v[0] for k, v in k_alone.items() if k != "comm")
     hideable = min(sum_x, sum_c)
+    compute_alone = sum(v[0] for k, v in k_alone.items() if k != "comm")
+    elementwise_alone = sum(k_alone[k][0] for k in ("rmsnorm", "resid_norm", "residual", "rope_kv", "swiglu"))
     overlap = {
         "t_iso_ms": t_iso, "t_iso_single_step": t_iso_single, "t_split_serial_ms": t_serial, "t_unsplit_ms": t_unsplit,
         "t_iso_nocomm_ms": t_iso_nocomm, "t_unsplit_nocomm_ms": t_unsplit_nocomm,
@@ -351,51 +358,77 @@ def main() -> int:
         "sum_copy_ms": sum_x, "sum_compute_ms": sum_c,
         "hidden_raw": (t_serial - t_iso) / sum_x if sum_x > 0 else None,
         "hidden_of_hideable": (t_serial - t_iso) / hideable if hideable > 0 else None,
+        "note": "hidden_raw = (T_serial - T_iso) / sum of copy times; hidden_of_hideable divides by min(copies, compute), "
+                "the most any schedule can hide; the 80 % target is read against hidden_of_hideable whenever the copies "
+                "outlast the compute (they cannot all be hidden then)",
+        "elementwise_share_of_compute": elementwise_alone / compute_alone if compute_alone > 0 else None,
     }
 
     # ---- the oracle on the host cores, bounded ---------------------------------------------------
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
+    cpu = None
+    if cpu_baseline:
         note("timing the CPU oracle on a bounded sample")
-        cpu_baseline = time_oracle(wl, x_cpu, w_cpu, split)
+        cpu = time_oracle(wl, x_cpu, w_cpu, split, L)
 
-    layer_flops = wl.gemm_flops() * L + attn_flops
-    result = {
-        "metric": "prefill tokens/s per layer shard (ISO vs unsplit) + attn/GEMM % MFMA peak",
-        "value": T / (t_iso * 1e-3), "unit": "tokens/s" if L == 1 else f"tokens/s through {L} layers", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": t_iso, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "hidden": H, "n_q_heads": nq, "n_kv_heads": nkv, "head_dim": d, "ffn": F,
-                   "seq": T, "split": split, "layers": L, "comm": "d2h copy of [Tc,hidden] at both points",
-                   "schedule": "two streams, chunk per stream"},
-        "tflops": layer_flops / (t_iso * 1e-3) / 1e12,
+    base.update({
         "tflops_compute_only": layer_flops / (t_iso_nocomm * 1e-3) / 1e12,
         "unsplit_tokens_per_s": T / (t_unsplit * 1e-3),
-        "layer_tokens_per_s": T * L / (t_iso * 1e-3),
         "roofline": roofline,
-        "cpu_baseline": cpu_baseline,
-        "int8_payload": {"t_iso_ms": t_iso_int8, "t_unsplit_ms": t_unsplit_int8,
+        "cpu_baseline": cpu,
+        "int8_payload": {"t_iso_ms": t_iso_int8, "t_unsplit_ms": t_unsplit_int8, "steps": Ks,
                          "tokens_per_s": T / (t_iso_int8 * 1e-3), "reduction_vs_unsplit": 1.0 - t_iso_int8 / t_unsplit_int8,
                          "sum_copy_ms": k_int8["comm"][0], "sum_quant_ms": k_int8["quant"][0],
                          "note": "partials quantised per token row to int8 before the copy (Section 3.2); "
                                  "not the headline: the headline moves the bf16 partial"},
         "fp8_projections": fp8,
-        "gemm_segmentation": dict(seg, note="Section 3.2: projections issued as 1, 2 or 4 launches along M; the copies "
-                                            "run on the DMA engines, so the contention this remedy addresses is "
-                                            "what gate_up_gemm.slowdown measures"),
-        "finer_splits": {"chunks": finer,
+        "gemm_segmentation": dict(seg, steps=Ks,
+                                  note="Section 3.2: projections issued as several launches along M; the copies "
+                                       "run on the DMA engines, so the contention this remedy addresses is "
+                                       "what gate_up_gemm.slowdown measures"),
+        "finer_splits": {"chunks": finer, "steps": Ks,
                          "note": "Section 6: cost-balanced cuts into more than two chunks; not the headline, which is "
                                  "the two-chunk schedule at the workload's split"},
         "overlap": overlap,
         "kernels_in_iso_schedule": pk_iso,
         "kernels_alone": pk_alone,
-    }
+    })
     ctx.close()
+    for w in layers:
+        for v in w.values():
+            v.free()
+    for a in (x0, x, kc, vc):
+        a.free()
+    return base
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding across GPUs); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import paper_2409_11155_amd as iso      # first: binds libiso to the HIP runtime it was built against
+    import iso_inputs
+
+    if iso.device_count() < 1:
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    wl = iso_inputs.WORKLOADS[args.workload]
+    L = args.layers if args.layers > 0 else wl.n_layers
+    full = wl.layer_flops() * L <= 1.0e13          # single layers up to 8k prompts: every variant at K steps
+    result = measure(iso, iso_inputs, args, args.workload, L, args.steps, args.warmup, args.split, full,
+                     not args.no_cpu_baseline)
+    if not (args.headline_only or args.no_side) and args.workload != SIDE_WORKLOAD:
+        note(f"side record: {SIDE_WORKLOAD}")
+        side = measure(iso, iso_inputs, args, SIDE_WORKLOAD, 1, args.steps, args.warmup, -1, True, False)
+        side.pop("metric", None)
+        result["side_" + SIDE_WORKLOAD] = side
     print(json.dumps(result))
     return 0
 
 
-def time_oracle(wl, x_cpu, w_cpu, split):
+def time_oracle(wl, x_cpu, w_cpu, split, L):
     """Times the CPU oracle, as it stands, on a bounded sample of the same workload."""
     import iso_inputs
     from oracle import iso_oracle as orc
@@ -407,7 +440,7 @@ def time_oracle(wl, x_cpu, w_cpu, split):
     sh = orc.LayerShape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.rms_eps, wl.rope_base)
     wn = {k: iso_inputs.to_f64(v, wl.dtype) for k, v in w_cpu.items()}
     xn = iso_inputs.to_f64(x_cpu, wl.dtype)
-    if wl.layer_flops() <= 1.0e12:
+    if wl.layer_flops() <= 1.0e12 and L == 1:
         # the whole layer fits the budget: repeat it until about ten seconds of CPU work are spent
         reps, spent, times = 0, 0.0, []
         while spent < 10.0 and reps < 25:
@@ -421,13 +454,25 @@ def time_oracle(wl, x_cpu, w_cpu, split):
         return {"value": wl.seq / med, "unit": "tokens/s", "cores": cores, "kind": "oracle",
                 "sample": f"full layer, all {wl.seq} tokens, layer_unsplit in float64 numpy: {reps} repetitions, "
                           f"{spent:.1f} s in all, median {med:.2f} s, fastest {times[0]:.2f} s"}
-    rows = 256
-    t0 = time.perf_counter()
-    orc.layer_rows(xn, wn, sh, list(range(0, wl.seq, wl.seq // rows))[:rows])
-    dt = time.perf_counter() - t0
-    return {"value": rows / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"layer_rows on {rows} evenly spaced output rows of {wl.seq} (K/V computed for all tokens), "
-                      f"{dt:.1f} s; value = sampled output rows per second, K/V for all tokens included"}
+    # Too large to run whole: the oracle's exact row-sampled form of ONE layer (K/V for every token, everything else
+    # for the sampled output rows) at two sample sizes; its time is linear in the number of rows, t = a + b * rows,
+    # so a full layer is a + b * T and the stack is L such layers.  Extrapolated, and labelled so.
+    T = wl.seq
+    r1, r2 = 64, 320
+    times = []
+    for r in (r1, r2):
+        rows = list(range(0, T, T // r))[:r]
+        t0 = time.perf_counter()
+        orc.layer_rows(xn, wn, sh, rows)
+        times.append(time.perf_counter() - t0)
+    b = max((times[1] - times[0]) / (r2 - r1), 1e-9)
+    a = max(times[0] - b * r1, 0.0)
+    t_layer = a + b * T
+    return {"value": T / (t_layer * L), "unit": "tokens/s" if L == 1 else f"tokens/s through {L} layers",
+            "cores": cores, "kind": "oracle", "extrapolated": True,
+            "sample": f"EXTRAPOLATED: layer_rows (float64 numpy) of layer 0 on {r1} and {r2} evenly spaced output rows of "
+                      f"{T}, K/V computed for all tokens: {times[0]:.1f} s and {times[1]:.1f} s -> t = {a:.2f} s + "
+                      f"{b * 1e3:.2f} ms per output row -> {t_layer:.1f} s for a full layer, times {L} layers"}
 
 
 if __name__ == "__main__":

@@ -141,8 +141,15 @@ int iso_plan_chunk_count(const iso_cfg *cfg, int T, int *n_chunks);
  * copy stand-in.  stream0/stream1 are the caller's two streams (stream1 may equal stream0; NULL is
  * the default stream).  On failure *out is NULL. */
 int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1);
-int iso_destroy(iso_ctx *ctx);            /* synchronises both streams, frees everything it owns */
-int iso_sync(iso_ctx *ctx);               /* waits for both streams                               */
+/* iso_sync waits for both streams.  iso_destroy synchronises the streams and frees everything the context owns.
+ * Both return ISO_ERR_HIP if a stream-K GEMM launched since the last iso_sync gave up a (bounded) wait for a
+ * partial tile: every result of that pass is then invalid.  The condition stays set until iso_sync has reported
+ * it; meanwhile the layer, attention and projection entry points refuse to enqueue further work (ISO_ERR_HIP). */
+int iso_destroy(iso_ctx *ctx);
+int iso_sync(iso_ctx *ctx);
+/* Host address of the pinned word behind that condition (0 = fine), NULL for an fp32 context.  For tests of the
+ * error path: a test writes 1 there instead of making a kernel time out. */
+unsigned *iso_streamk_status_word(iso_ctx *ctx);
 const char *iso_last_error(void);         /* message for the calling thread's last failure        */
 
 /* One decoder-layer shard over a prompt of T tokens (Section 2.2 for the block structure, Section 3.1
@@ -267,12 +274,14 @@ int iso_gemm_fp8(iso_ctx *ctx, const void *a8, const float *sa, const void *w8, 
 
 /* GEMM segmentation (Section 3.2, the remedy for the computation-dominated case): every projection of the layer
  * entry points is issued as n launches over consecutive row ranges (multiples of 256 rows; products with fewer
- * than 256 * n rows stay whole).  Results are unchanged bit for bit except where the stream-K kernel is picked
- * for one size and not the other.  n in [1, 16]; 1 (the default) is one launch.  Errors: NULL, ISO_ERR_SHAPE. */
+ * than 256 * n rows stay whole).  Results are the same bits as long as the segments take the same kernel variant
+ * as the whole product (the launch rule looks at the tile count, so a segment may get the 128x128 tile or miss the
+ * stream-K launch where the whole product does not; the sum order inside a tile then differs) and agree within
+ * rounding otherwise.  n in [1, 16]; 1 (the default) is one launch.  Errors: NULL, ISO_ERR_SHAPE. */
 int iso_set_gemm_segments(iso_ctx *ctx, int n);
 
 /* Per-launch timing for measurement.  While enabled, every kernel launch and every copy the library
- * enqueues is bracketed by a pair of HIP events recorded in the stream of that launch (at most 8192
+ * enqueues is bracketed by a pair of HIP events recorded in the stream of that launch (at most 65536
  * launches are kept; enabling clears the record).  iso_timing_read synchronises both streams and returns
  * the summed duration and the number of recorded launches of one kind. */
 typedef enum {

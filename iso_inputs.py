@@ -152,6 +152,11 @@ def make_workload_inputs(w: Workload, seed: int = 0, layer: int = 0):
     return x, weights
 
 
+def make_workload_inputs_layer(w: Workload, seed: int = 0, layer: int = 0) -> Dict[str, np.ndarray]:
+    """The weights of layer `layer` of a named workload alone (same draws as make_workload_inputs)."""
+    return make_layer(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, 1000 * seed + layer, w.dtype)
+
+
 def make_qkv_cache(tc: int, kv_len: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
                    seed: int, dtype: str):
     """Random q[tc, nq, d], k[kv_len, nkv, d], v[kv_len, nkv, d] for attention-only tests."""

@@ -426,7 +426,7 @@ bool iso_attn_bf16_dtl_supported(int d, int kv_len, int nkv) {
 hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v, void *out, int Tc, int q_offset,
                                     int kv_len, int nq, int nkv, int d, int q_stride, int shape, hipStream_t s) {
     if (d != D) return hipErrorInvalidValue;
-    static unsigned long long lds_allowed[2] = {0, 0};
+    static iso_dev_mask lds_allowed[2];
     if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(attn_bf16_dtl_kernel<2, 1, false>), 2 * STAGE_B, &lds_allowed[0]);
         e != hipSuccess)
         return e;
@@ -441,15 +441,7 @@ hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v,
     // work -- provided the halved count fills its last round of the chip to 90 % (measured 1.05-1.36x; a three-quarter
     // full third round loses instead).  Larger launches balance by themselves (longest row blocks first) and run two
     // independent workgroups per unit (3-8 % better there).
-    static int ncu_of[64] = {0};             // compute units per device, looked up once
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
-    if (ncu_of[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-        ncu_of[dev] = n;
-    }
-    const int ncu = ncu_of[dev];
+    const int ncu = iso_num_cu();
     const long long paired = (long long)((n_blocks + 1) / 2) * nq;
     const long long rounds = (paired + ncu - 1) / ncu;
     const bool pair_ok = wgs >= 320 && wgs <= 2048 && (paired <= ncu || paired * 10 >= 9 * rounds * ncu);

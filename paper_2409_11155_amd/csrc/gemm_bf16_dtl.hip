@@ -63,11 +63,16 @@ template <int BM, int BN, int WM, int WN> struct DtlCfg {
 // SK = true (stream-K): the grid is one workgroup per compute unit and the (tile, k-slice) units are dealt out in
 // equal contiguous spans, so a launch whose tile count does not fill the chip still keeps every unit busy.  A span
 // that stops inside a tile leaves an fp32 partial tile in the workspace slot of its workgroup and raises that
-// workgroup's flag; the workgroup that reaches the tile's last k-slice adds the partials (in workgroup order, so
-// the sum is reproducible) and writes the tile.  Every workgroup does its partial segment FIRST and only then its
-// finishing segments (the one that needs partials last), and a finisher only ever waits for workgroups with a lower index, which the dispatcher
-// started earlier and which never wait before raising their flag: the waits always end.  They are bounded as
-// well: a wait that exceeds the spin limit reports through *sk_err and carries on.
+// workgroup's flag; the workgroup that reaches the tile's last k-slice adds the partials (in team order, so the sum
+// is reproducible) and writes the tile.  Progress: every workgroup does its partial segment FIRST and raises its flag
+// before it waits for anything, so a workgroup that has been dispatched always publishes its partial; a finisher
+// waits only for teams with a lower number, and both mappings place team q - 1 at a lower workgroup id than team q,
+// i.e. at a workgroup the dispatcher started earlier.  The grid never exceeds the compute units of the device and a
+// workgroup takes a whole unit, so on an otherwise idle chip all of them are resident; beside other kernels a
+// workgroup may have to wait for a unit, but only behind kernels that end by themselves or behind stream-K
+// workgroups whose own waits point at workgroups dispatched before them.  Every wait is bounded as well: one that
+// exceeds the spin limit raises *sk_err (a pinned host word that the library reads at its next entry point and in
+// iso_sync) and carries on with a wrong tile.
 template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE, bool SK, bool M16 = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_t *__restrict__ A,
                                                                      const bf16_t *__restrict__ W,
@@ -395,16 +400,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
         const int TS = sk_team, bid = blockIdx.x;
         const int GT = gridDim.x / TS;
         int q, r;                                // team, member
-        const int tpx = GT >> 3;                 // teams per XCD (grouped mapping)
-        if (sk_grouped) {                        // team members and neighbouring teams share an XCD
-            const int idx = bid >> 3;
-            q = (bid & 7) * tpx + idx / TS;
+        if (sk_grouped) {                        // team members share an XCD (workgroup ids go round-robin over the 8
+            const int idx = bid >> 3;            // XCDs); team q - 1 sits at a lower workgroup id than team q
+            q = (idx / TS) * 8 + (bid & 7);
             r = idx % TS;
         } else {
             q = bid / TS;
             r = bid % TS;
         }
-        auto wg_of = [&](int qq) { return sk_grouped ? ((qq % tpx) * TS + r) * 8 + qq / tpx : qq * TS + r; };
+        auto wg_of = [&](int qq) { return sk_grouped ? ((qq >> 3) * TS + r) * 8 + (qq & 7) : qq * TS + r; };
         const int ngm = (tiles_m + TS - 1) / TS;
         const long long U = (long long)ngm * tiles_n * nk;
         auto span_begin = [&](int j) { return (int)(U * j / GT); };
@@ -513,7 +517,7 @@ template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE, bool M16 = fal
 hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     using Cfg = DtlCfg<BM, BN, WM, WN>;
     constexpr int LDS_BYTES = (PIPE && Cfg::W3) ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
-    static unsigned long long lds_allowed = 0;
+    static iso_dev_mask lds_allowed{0};
     auto kern = gemm_bf16_dtl_kernel<BM, BN, WM, WN, SWIGLU, PIPE, false, M16>;
     if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), LDS_BYTES, &lds_allowed); e != hipSuccess)
         return e;
@@ -534,7 +538,7 @@ template <bool SWIGLU>
 hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K, iso_sk_ws *sk, hipStream_t s) {
     using Cfg = DtlCfg<256, 256, 4, 2>;
     constexpr int LDS_BYTES = Cfg::W3 ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
-    static unsigned long long lds_allowed = 0;
+    static iso_dev_mask lds_allowed{0};
     auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, SWIGLU, true, true>;
     if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), LDS_BYTES, &lds_allowed); e != hipSuccess)
         return e;

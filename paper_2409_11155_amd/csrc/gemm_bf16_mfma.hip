@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(const bf16_t *__res
 template <int BM, int BN, int BK>
 hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hipStream_t s) {
     using Cfg = GemmCfg<BM, BN, BK>;
-    static unsigned long long lds_allowed = 0;
+    static iso_dev_mask lds_allowed{0};
     auto kern = gemm_bf16_mfma_kernel<BM, BN, BK>;
     if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), (int)Cfg::LDS_BYTES, &lds_allowed); e != hipSuccess)
         return e;

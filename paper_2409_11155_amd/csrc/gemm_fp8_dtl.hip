@@ -329,16 +329,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_fp8_dtl_kernel(const unsign
         const int TS = sk_team, bid = blockIdx.x;
         const int GT = gridDim.x / TS;
         int q, r;                                // team, member
-        const int tpx = GT >> 3;                 // teams per XCD (grouped mapping)
-        if (sk_grouped) {                        // team members and neighbouring teams share an XCD
-            const int idx = bid >> 3;
-            q = (bid & 7) * tpx + idx / TS;
+        if (sk_grouped) {                        // team members share an XCD (workgroup ids go round-robin over the 8
+            const int idx = bid >> 3;            // XCDs); team q - 1 sits at a lower workgroup id than team q
+            q = (idx / TS) * 8 + (bid & 7);
             r = idx % TS;
         } else {
             q = bid / TS;
             r = bid % TS;
         }
-        auto wg_of = [&](int qq) { return sk_grouped ? ((qq % tpx) * TS + r) * 8 + qq / tpx : qq * TS + r; };
+        auto wg_of = [&](int qq) { return sk_grouped ? ((qq >> 3) * TS + r) * 8 + (qq & 7) : qq * TS + r; };
         const int ngm = (tiles_m + TS - 1) / TS;
         const long long U = (long long)ngm * tiles_n * nk;
         auto span_begin = [&](int j) { return (int)(U * j / GT); };
@@ -434,7 +433,7 @@ template <int BM, int BN, int WM, int WN, bool SWIGLU>
 hipError_t launch(const void *a, const void *w, const float *sa, const float *sw, void *c, int M, int N, int K,
                   hipStream_t s) {
     using Cfg = F8Cfg<BM, BN, WM, WN>;
-    static unsigned long long lds_allowed = 0;
+    static iso_dev_mask lds_allowed{0};
     auto kern = gemm_fp8_dtl_kernel<BM, BN, WM, WN, SWIGLU, false>;
     if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), Cfg::LDS_BYTES, &lds_allowed); e != hipSuccess)
         return e;
@@ -450,7 +449,7 @@ template <bool SWIGLU>
 hipError_t launch_sk(const void *a, const void *w, const float *sa, const float *sw, void *c, int M, int N, int K,
                      iso_sk_ws *sk, hipStream_t s) {
     using Cfg = F8Cfg<256, 256, 4, 2>;
-    static unsigned long long lds_allowed = 0;
+    static iso_dev_mask lds_allowed{0};
     auto kern = gemm_fp8_dtl_kernel<256, 256, 4, 2, SWIGLU, true>;
     if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), Cfg::LDS_BYTES, &lds_allowed); e != hipSuccess)
         return e;

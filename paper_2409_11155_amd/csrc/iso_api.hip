@@ -216,6 +216,16 @@ int attention(iso_ctx *ctx, const void *q, int q_stride, const void *kc, const v
         if (r_ != ISO_OK) return r_; \
     } while (0)
 
+// The stream-K GEMM reports a wait that ran out through a pinned host word.  It stays set until iso_sync has
+// returned the error: the layer, attention and projection entry points look at it before they enqueue anything, so
+// that a pass whose results are invalid is not followed by hundreds of launches that build on them.
+int sk_status(const iso_ctx *ctx) {
+    if (ctx->sk[0].err && *(volatile unsigned *)ctx->sk[0].err)
+        return fail(ISO_ERR_HIP, "stream-K GEMM: a wait for a partial tile ran out in an earlier launch; results since "
+                                 "the last iso_sync are invalid (iso_sync reports and clears this)");
+    return ISO_OK;
+}
+
 
 // Communication point of one chunk: nothing, the [n, H] partial as it is, or its int8 codes + row scales.
 // `which` = 0 after o_proj, 1 after down; the host sink keeps the two points apart.
@@ -370,7 +380,7 @@ int check_layer_args(iso_ctx *ctx, const iso_weights *layers, int n_layers, void
         return fail(ISO_ERR_SHAPE, "unknown comm mode %d", comm);
     if (sched != ISO_SCHED_OVERLAP && sched != ISO_SCHED_SERIAL && sched != ISO_SCHED_STREAM_PER_CHUNK)
         return fail(ISO_ERR_SHAPE, "unknown schedule %d", sched);
-    return ISO_OK;
+    return sk_status(ctx);
 }
 
 // Extra streams for ISO_SCHED_STREAM_PER_CHUNK, created on first use (default priority, like every stream here).
@@ -607,6 +617,8 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
                      hip_ok(hipMemset(ctx->sk[i].base, 0, 4096), "hipMemset(stream-K flags)");
             }
             if (!ok) break;
+            // the memsets ran on the null stream, which the library's non-blocking streams do not wait for
+            if (!hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize")) break;
         }
         if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming), "event")) break;
         {
@@ -644,7 +656,11 @@ int iso_destroy(iso_ctx *ctx) {
     if (ctx->ws) {   // only a fully or partly built context has device state to drain
         (void)hipStreamSynchronize(ctx->stream[0]);
         if (ctx->stream[1] != ctx->stream[0]) (void)hipStreamSynchronize(ctx->stream[1]);
+        for (int k = 0; k < ISO_MAX_CHUNKS; ++k)
+            if (ctx->xstream[k]) (void)hipStreamSynchronize(ctx->xstream[k]);
     }
+    // everything is freed either way; the return value says whether the last pass before the teardown was valid
+    const int rc = ctx->sk[0].err ? sk_status(ctx) : (int)ISO_OK;
     for (int i = 0; i < ctx->n_tev_created; ++i) {
         (void)hipEventDestroy(ctx->tev0[i]);
         (void)hipEventDestroy(ctx->tev1[i]);
@@ -666,7 +682,7 @@ int iso_destroy(iso_ctx *ctx) {
     if (ctx->rope_sin) (void)hipFree(ctx->rope_sin);
     if (ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
-    return ISO_OK;
+    return rc;
 }
 
 int iso_gemm_launch_plan(int M, int N, int K, int num_cu, int *kind, int *team, int *grid) {
@@ -711,6 +727,7 @@ int iso_gemm_fp8(iso_ctx *ctx, const void *a8, const float *sa, const void *w8, 
     if (!a8 || !sa || !w8 || !sw || !c) return fail(ISO_ERR_NULL, "operands, scales and c must be non-NULL");
     if (ctx->cfg.dtype != ISO_BF16) return fail(ISO_ERR_DTYPE, "the FP8 GEMM writes bf16");
     if (!iso_gemm_fp8_supported(M, N, K)) return fail(ISO_ERR_SHAPE, "M=%d N=%d K=%d: need M >= 1, N %% 8 == 0, K %% 128 == 0", M, N, K);
+    ISO_TRY(sk_status(ctx));
     Timed t_(ctx, ISO_K_GEMM_O, (hipStream_t)stream);
     hipError_t e = iso_launch_gemm_fp8(a8, sa, w8, sw, c, M, N, K, (ctx->flags >> 8) & 15, sk_for(ctx, (hipStream_t)stream),
                                        (hipStream_t)stream);
@@ -804,6 +821,7 @@ int iso_copy_d2h(void *dst, const void *src, size_t bytes) {
 int iso_copy_d2d(void *dst, const void *src, size_t bytes) {
     if (!dst || !src) return fail(ISO_ERR_NULL, "dst and src must be non-NULL");
     HIP_TRY(hipMemcpy(dst, src, bytes, hipMemcpyDeviceToDevice));
+    HIP_TRY(hipDeviceSynchronize());   // a device-to-device hipMemcpy may return before the copy has run
     return ISO_OK;
 }
 int iso_stream_create(void **stream) {
@@ -858,6 +876,7 @@ int iso_attn_chunk(iso_ctx *ctx, const void *q, const void *k_cache, const void 
     if (kv_len < 1) return fail(ISO_ERR_SHAPE, "kv_len=%d must be positive", kv_len);
     if (kv_len > ctx->cfg.max_seq) return fail(ISO_ERR_WORKSPACE, "kv_len=%d exceeds max_seq=%d", kv_len, ctx->cfg.max_seq);
     if (Tc > ctx->cfg.max_seq) return fail(ISO_ERR_WORKSPACE, "Tc=%d exceeds max_seq=%d", Tc, ctx->cfg.max_seq);
+    ISO_TRY(sk_status(ctx));
     return attention(ctx, q, ctx->cfg.n_q_heads * ctx->cfg.head_dim, k_cache, v_cache, out, Tc, q_offset, kv_len,
                      (hipStream_t)stream);
 }
@@ -868,6 +887,7 @@ int iso_gemm_rowpar(iso_ctx *ctx, const void *a, const void *w, void *c, int M, 
     if (!a || !w || !c) return fail(ISO_ERR_NULL, "a, w and c must be non-NULL");
     if (M < 1 || N < 1 || K < 1) return fail(ISO_ERR_SHAPE, "M=%d N=%d K=%d must be positive", M, N, K);
     if (ctx->cfg.dtype == ISO_BF16 && (K % 8)) return fail(ISO_ERR_SHAPE, "K=%d must be a multiple of 8 for bf16", K);
+    ISO_TRY(sk_status(ctx));
     ISO_TRY(gemm(ctx, ISO_K_GEMM_O, a, w, c, M, N, K, (hipStream_t)stream));
     if (host_sink) {
         Timed t_(ctx, ISO_K_COMM, (hipStream_t)stream);
@@ -875,6 +895,8 @@ int iso_gemm_rowpar(iso_ctx *ctx, const void *a, const void *w, void *c, int M, 
     }
     return ISO_OK;
 }
+
+unsigned *iso_streamk_status_word(iso_ctx *ctx) { return ctx ? ctx->sk[0].err : nullptr; }
 
 int iso_rmsnorm(iso_ctx *ctx, const void *x, const void *g, void *y, int T, void *stream) {
     if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");

@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "iso.h"
 
 typedef __bf16 bf16_t;
@@ -57,7 +59,7 @@ struct iso_ctx {
     hipEvent_t *tev0, *tev1;
     int *tkind;
 };
-constexpr int ISO_MAX_TIMED = 8192;
+constexpr int ISO_MAX_TIMED = 65536;
 
 // ---- launchers; each validates nothing (callers do) and returns the launch status -------------
 hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta_or_null, void *x_out_or_null,
@@ -114,15 +116,29 @@ __device__ __forceinline__ float iso_wave_sum(float v) {
 }
 // Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the function on the device that is
 // current when it is set).  `done` is the caller's static mask of devices already served; ids beyond 63 are set every
-// time.  Called from launchers only.
-inline hipError_t iso_allow_lds(const void *kernel, int bytes, unsigned long long *done) {
+// time.  Called from launchers only; host threads may race here (setting the attribute twice is harmless, the mask is
+// atomic).
+typedef std::atomic<unsigned long long> iso_dev_mask;
+inline hipError_t iso_allow_lds(const void *kernel, int bytes, iso_dev_mask *done) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64 && ((*done >> dev) & 1ull)) return hipSuccess;
+    if (dev >= 0 && dev < 64 && ((done->load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess && dev >= 0 && dev < 64) *done |= 1ull << dev;
+    if (e == hipSuccess && dev >= 0 && dev < 64) done->fetch_or(1ull << dev, std::memory_order_release);
     return e;
+}
+// Compute units of the current device (looked up once per device; 256 if the query fails).
+inline int iso_num_cu(void) {
+    static std::atomic<int> ncu_of[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    int n = ncu_of[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        ncu_of[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
 }
 
 __device__ __forceinline__ float iso_wave_max(float v) {

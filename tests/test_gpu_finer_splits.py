@@ -110,11 +110,15 @@ def test_full_size_30b_tp4_2k_cost_balanced_chunks_sampled_rows(n_chunks, sched)
 
 def test_gemm_segmentation_leaves_the_layer_unchanged():
     """Section 3.2: projections issued as several launches along M.  Each output row depends on its own input row
-    only and the tile kernels' per-row arithmetic does not depend on the row's tile, so the layer output is the
-    same bits for 1, 2 and 3 launches (stream-K off: it would pick a different sum order for different sizes)."""
+    only and the tile kernels' per-row arithmetic does not depend on the row's tile, so with the same kernel variant
+    the layer output is the same bits for 1, 2 and 3 launches (stream-K off: it would pick a different sum order for
+    different sizes) -- and every one of them is the oracle's layer within the bf16 bound.  With stream-K left on the
+    segments may take another launch than the whole product: same bound against the oracle, bits not compared."""
     hidden, nq, nkv, d, ffn, T, dt = 1024, 8, 1, 128, 1024, 1536, "bf16"
-    w = [iso.upload_weights(iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=8, dtype=dt), dt)]
+    w_host = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=8, dtype=dt)
+    w = [iso.upload_weights(w_host, dt)]
     x = iso_inputs.make_hidden(T, hidden, seed=8, dtype=dt)
+    ref = orc.layer_unsplit(h64(x, dt), oracle_weights(w_host, dt), shape_of(hidden, nq, nkv, d, ffn))["x_out"]
     with make_ctx(hidden, nq, nkv, d, ffn, dt, T) as ctx:
         ctx.set_flags(iso.ISO_FLAG_NO_STREAMK)
         outs = []
@@ -122,11 +126,44 @@ def test_gemm_segmentation_leaves_the_layer_unchanged():
             ctx.set_gemm_segments(n_seg)
             out, _, _ = run_chunks(ctx, w, x, dt, T, [768], nkv, d, T, iso.ISO_COMM_D2H, iso.ISO_SCHED_OVERLAP)
             outs.append(out.numpy())
+            err = orc.max_rel_err(h64(outs[-1], dt), ref)
+            assert err <= TOL_LAYER[dt], (n_seg, err)
         np.testing.assert_array_equal(outs[1], outs[0])
         np.testing.assert_array_equal(outs[2], outs[0])
+        ctx.set_flags(0)                                   # stream-K chosen by the launch rule where it applies
+        for n_seg in (1, 2):
+            ctx.set_gemm_segments(n_seg)
+            out, _, _ = run_chunks(ctx, w, x, dt, T, [768], nkv, d, T, iso.ISO_COMM_D2H, iso.ISO_SCHED_OVERLAP)
+            err = orc.max_rel_err(f64(out), ref)
+            assert err <= TOL_LAYER[dt], ("stream-K allowed", n_seg, err)
         with pytest.raises(iso.IsoError) as ei:
             ctx.set_gemm_segments(0)
         assert ei.value.code == iso.ISO_ERR_SHAPE
+
+
+def test_gemm_segmentation_across_a_change_of_tile_variant():
+    """A case where the whole product and its segments take different kernels: o_proj and down at M = 4096, N = 2048
+    are 128 tiles of 256 x 256 (the 256-wide tile with 16x16x32 matrix instructions), each half of 2048 rows is 64
+    tiles and takes the 128-wide tile with 32x32x16 instructions (the launch plan is asserted, not assumed).  The two
+    outputs need not agree in bits; each must be the oracle's layer on sampled rows."""
+    hidden, nq, nkv, d, ffn, T, dt = 2048, 16, 2, 128, 2048, 4096, "bf16"
+    assert iso.gemm_launch_plan(T, hidden, nq * d, 0)[0] == iso.ISO_GEMM_TILE_256
+    assert iso.gemm_launch_plan(T // 2, hidden, nq * d, 0)[0] == iso.ISO_GEMM_TILE_128
+    w_host = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=9, dtype=dt)
+    w = [iso.upload_weights(w_host, dt)]
+    x = iso_inputs.make_hidden(T, hidden, seed=9, dtype=dt)
+    rows = iso_inputs.sample_rows(T, 0, 48, seed=3)
+    ref = orc.layer_rows(h64(x, dt), oracle_weights(w_host, dt), shape_of(hidden, nq, nkv, d, ffn), rows)["x_out"]
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, T) as ctx:
+        ctx.set_flags(iso.ISO_FLAG_NO_STREAMK)
+        outs = []
+        for n_seg in (1, 2):
+            ctx.set_gemm_segments(n_seg)
+            out, _, _ = run_chunks(ctx, w, x, dt, T, [], nkv, d, T, iso.ISO_COMM_D2H, iso.ISO_SCHED_SERIAL)
+            outs.append(out.numpy())
+            err = orc.max_rel_err(h64(outs[-1], dt)[rows], ref)
+            assert err <= TOL_LAYER[dt], (n_seg, err)
+        print("segments across a tile-variant change: bits equal =", bool(np.array_equal(outs[0], outs[1])))
 
 
 def test_chunked_prefill_rejects_bad_arguments():
