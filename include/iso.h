@@ -205,6 +205,20 @@ int iso_attn_chunk(iso_ctx *ctx, const void *q, const void *k_cache, const void 
 int iso_gemm_rowpar(iso_ctx *ctx, const void *a, const void *w, void *c, int M, int N, int K,
                     void *stream, void *host_sink);
 
+/* iso_gemm_rowpar for callers that cannot allocate or record memset nodes: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  c[M, N] = a[M, K] * w[N, K]^T (bf16, no host copy) through the
+ * stream-K kernel, whose flag words and fp32 partial tiles live in a static device array of 4 KiB + 256 * 256 KiB
+ * (64 MiB + 4 KiB) that every GPU the library runs on holds until the process ends; its address on a device is
+ * looked up when the first bf16 context is created there.  The call enqueues two kernels on `stream` (one clears the
+ * flag words, then the product) and calls no allocating routine, no hipMemsetAsync and no event creation; it is not
+ * part of the per-launch timing record.  Limits: bf16 context; K a multiple of 64, N a multiple of 8, M*K and N*K
+ * below 2^31 elements (ISO_ERR_SHAPE otherwise); at most 256 workgroups are used whatever the device.  All calls on
+ * one GPU share the array: calls that may overlap in time (different streams, different contexts, different host
+ * threads) race on it and must be ordered by the caller; calls in one stream are ordered by the stream.  A wait that
+ * runs out is reported as for every stream-K launch (iso_sync).
+ * Errors: NULL, ISO_ERR_DTYPE (fp32 context), ISO_ERR_SHAPE, ISO_ERR_HIP. */
+int iso_gemm_rowpar_static(iso_ctx *ctx, const void *a, const void *w, void *c, int M, int N, int K, void *stream);
+
 /* The element-wise steps of the layer, exposed for parity tests and per-kernel measurement.
  * All pointers are device pointers of cfg.dtype; `stream` is a hipStream_t.                     */
 /* y[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g */

@@ -38,7 +38,7 @@ EXPORTS = [
     "iso_timing_enable", "iso_timing_read",
     "iso_device_count", "iso_device_sync", "iso_dev_alloc", "iso_dev_free", "iso_dev_fill", "iso_host_alloc",
     "iso_host_free", "iso_copy_h2d", "iso_copy_d2h", "iso_copy_d2h_async", "iso_set_gemm_segments", "iso_quantize_rows_fp8", "iso_rmsnorm_fp8", "iso_gemm_fp8", "iso_gemm_launch_plan", "iso_copy_d2d", "iso_stream_create", "iso_stream_destroy",
-    "iso_streamk_status_word",
+    "iso_gemm_rowpar_static", "iso_streamk_status_word",
 ]
 KERNEL_KINDS = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn", "rmsnorm", "resid_norm", "residual",
                 "rope_kv", "swiglu", "comm", "quant"]
@@ -107,6 +107,7 @@ def load() -> ctypes.CDLL:
                                              ci, ci]
     lib.iso_attn_chunk.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp]
     lib.iso_gemm_rowpar.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp, vp]
+    lib.iso_gemm_rowpar_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
     lib.iso_streamk_status_word.argtypes = [vp]
     lib.iso_streamk_status_word.restype = ctypes.POINTER(ctypes.c_uint)
     lib.iso_rmsnorm.argtypes = [vp, vp, vp, vp, ci, vp]
@@ -461,6 +462,9 @@ class Context:
     def gemm_rowpar(self, a, w, c, M: int, N: int, K: int, stream=None, host_sink: Optional[int] = None) -> None:
         _check(self._lib.iso_gemm_rowpar(self._h, _ptr(a), _ptr(w), _ptr(c), M, N, K, _stream_handle(stream),
                                          host_sink))
+
+    def gemm_rowpar_static(self, a, w, c, M: int, N: int, K: int, stream=None) -> None:
+        _check(self._lib.iso_gemm_rowpar_static(self._h, _ptr(a), _ptr(w), _ptr(c), M, N, K, _stream_handle(stream)))
 
     def streamk_status_word(self):
         """ctypes pointer to the pinned status word of the stream-K GEMM (None for an fp32 context)."""

@@ -22,6 +22,14 @@
 #include "iso_internal.h"
 #include <type_traits>
 
+// Stream-K workspace of the entry point that allocates nothing (iso_gemm_rowpar_static): flag words (4 KiB) and one
+// fp32 partial tile of 256 x 256 for each of at most 256 workgroups.  Every GPU the library runs on holds its own
+// copy of this array, at its own address, until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the per-device address looked up in iso_gemm_static_setup.
+#define ISO_STATIC_SK_MAX_WG 256
+#define ISO_STATIC_SK_BYTES (4096 + (size_t)ISO_STATIC_SK_MAX_WG * 256 * 256 * 4)
+static __device__ __align__(256) unsigned char scratch[ISO_STATIC_SK_BYTES];
+
 namespace {
 
 constexpr int BK = 64;                 // k slice: 128 bytes per row
@@ -552,7 +560,65 @@ hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K,
     return hipGetLastError();
 }
 
+// ---- stream-K launch whose workspace is the static device array above
+std::atomic<unsigned char *> g_static_ptr[64];      // per device: address of `scratch` on that device
+iso_dev_mask g_static_lds{0};
+
+__global__ void sk_clear_flags_kernel(unsigned *flags, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) flags[i] = 0u;
+}
+
 }  // namespace
+
+size_t iso_gemm_static_scratch_bytes(void) { return ISO_STATIC_SK_BYTES; }
+
+// Once per device, with that device current (iso_create calls it): looks up the device address of the static
+// workspace and raises the stream-K kernel's LDS limit, so that the entry point itself only launches.
+hipError_t iso_gemm_static_setup(void) {
+    int dev = -1;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (g_static_ptr[dev].load(std::memory_order_acquire)) return hipSuccess;
+    void *p = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    using Cfg = DtlCfg<256, 256, 4, 2>;
+    auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, false, true, true>;
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), Cfg::W3 ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES,
+                                     &g_static_lds);
+        e != hipSuccess)
+        return e;
+    g_static_ptr[dev].store((unsigned char *)p, std::memory_order_release);
+    return hipSuccess;
+}
+
+// c = a w^T through the stream-K kernel with the static workspace of the current device.  Two launches, no
+// allocation, no memset node: a small kernel clears the flag words the launch uses (the array keeps the last call's
+// contents), then the GEMM runs with launch number 1.  hipErrorNotReady if iso_gemm_static_setup has not run on this
+// device.
+hipError_t iso_launch_gemm_bf16_sk_static(const void *a, const void *w, void *c, int M, int N, int K, unsigned *err_word,
+                                          hipStream_t s) {
+    int dev = -1;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    unsigned char *ptr = g_static_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) return hipErrorNotReady;
+    using Cfg = DtlCfg<256, 256, 4, 2>;
+    constexpr int LDS_BYTES = Cfg::W3 ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
+    int ncu = iso_num_cu();
+    if (ncu > ISO_STATIC_SK_MAX_WG) ncu = ISO_STATIC_SK_MAX_WG;
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    int TS, G, grouped;
+    sk_plan(M, N, K, ncu, &TS, &G, &grouped);
+    if (G < 1 || G > ISO_STATIC_SK_MAX_WG) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(sk_clear_flags_kernel, dim3((G + 255) / 256), dim3(256), 0, s, reinterpret_cast<unsigned *>(ptr), G);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, false, true, true>;
+    hipLaunchKernelGGL(kern, dim3(G), dim3(Cfg::NT), LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
+                       K, tiles_m, tiles_n, ptr, 1u, err_word, TS, grouped);
+    return hipGetLastError();
+}
 
 // Stream-K launch shape for an M x N product of nk k-slices on num_wg compute units (shared by the bf16 and FP8
 // kernels).  Team size: the largest power of two (at most 8) that tiles the tile rows without idle members; the grouped

@@ -619,6 +619,8 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
             if (!ok) break;
             // the memsets ran on the null stream, which the library's non-blocking streams do not wait for
             if (!hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize")) break;
+            // static workspace of iso_gemm_rowpar_static: address on this device, kernel attributes
+            if (!hip_ok(iso_gemm_static_setup(), "static stream-K workspace")) break;
         }
         if (!hip_ok(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming), "event")) break;
         {
@@ -893,6 +895,21 @@ int iso_gemm_rowpar(iso_ctx *ctx, const void *a, const void *w, void *c, int M, 
         Timed t_(ctx, ISO_K_COMM, (hipStream_t)stream);
         HIP_TRY(hipMemcpyAsync(host_sink, c, (size_t)M * N * ctx->elt, hipMemcpyDeviceToHost, (hipStream_t)stream));
     }
+    return ISO_OK;
+}
+
+int iso_gemm_rowpar_static(iso_ctx *ctx, const void *a, const void *w, void *c, int M, int N, int K, void *stream) {
+    if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
+    if (!a || !w || !c) return fail(ISO_ERR_NULL, "a, w and c must be non-NULL");
+    if (ctx->cfg.dtype != ISO_BF16) return fail(ISO_ERR_DTYPE, "the static-workspace GEMM takes bf16 operands");
+    if (M < 1 || N < 1 || K < 1) return fail(ISO_ERR_SHAPE, "M=%d N=%d K=%d must be positive", M, N, K);
+    if (!iso_gemm_bf16_dtl_supported(M, N, K))
+        return fail(ISO_ERR_SHAPE, "M=%d N=%d K=%d is beyond what the static-workspace GEMM takes: K a multiple of 64, "
+                                   "N a multiple of 8, M*K and N*K below 2^31 elements", M, N, K);
+    ISO_TRY(sk_status(ctx));
+    hipError_t e = iso_launch_gemm_bf16_sk_static(a, w, c, M, N, K, ctx->sk[0].err, (hipStream_t)stream);
+    if (e == hipErrorNotReady) return fail(ISO_ERR_HIP, "no context has been created on the current device");
+    if (e != hipSuccess) return fail(ISO_ERR_HIP, "static-workspace gemm launch (M=%d N=%d K=%d): %s", M, N, K, hipGetErrorString(e));
     return ISO_OK;
 }
 

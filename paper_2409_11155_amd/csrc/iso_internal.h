@@ -91,6 +91,11 @@ hipError_t iso_launch_gemm_fp8(const void *a8, const float *sa, const void *w8, 
                                int K, int variant, iso_sk_ws *sk_or_null, hipStream_t s);
 hipError_t iso_launch_gemm_swiglu_fp8(const void *a8, const float *sa, const void *w8, const float *sw, void *act, int M,
                                       int F, int K, int variant, iso_sk_ws *sk_or_null, hipStream_t s);
+// stream-K with the workspace in a static device array (no allocation at call time)
+hipError_t iso_gemm_static_setup(void);     // once per device, with that device current
+size_t iso_gemm_static_scratch_bytes(void);
+hipError_t iso_launch_gemm_bf16_sk_static(const void *a, const void *w, void *c, int M, int N, int K, unsigned *err_word,
+                                          hipStream_t s);
 // stream-K launch shape for nk k-slices (team size, grid, grouped mapping); returns the k-slices per team
 long long iso_gemm_sk_plan(int M, int N, int nk, int num_wg, int *team, int *grid, int *grouped);
 hipError_t iso_launch_attn_simple(int dtype, const void *q, const void *k, const void *v, void *out, int Tc,
