@@ -249,6 +249,8 @@ enum {
     /* bits 12..13: launch shape of the direct-to-LDS attention (0 = chosen from the size; 1 = key tiles split inside
      * the workgroup; 2 = that, and two row blocks (longest with shortest) per workgroup; 3 = one row block per
      * workgroup, two workgroups per compute unit) */
+    /* bits 14..16: key split of the direct-to-LDS attention ACROSS workgroups (0 = chosen from the size: launches of at
+     * most half as many workgroups as the device has compute units; 1 = never; 2, 3, 4 = that many shares) */
 };
 int iso_set_flags(iso_ctx *ctx, int flags);
 

@@ -25,6 +25,11 @@ constexpr int BN = 64;             // keys per tile
 constexpr int ROW_B = D * 2;       // bytes per K/V row in LDS
 constexpr int TILE_B = BN * ROW_B; // 16 KB
 constexpr int STAGE_B = 2 * TILE_B;
+// Key split across workgroups (launches that leave most compute units idle): one partial state of a row block =
+// 16 float4 of unnormalised output + (running maximum, partial sum) for each of the 256 lanes that hold it.
+constexpr int PART_O_BYTES = 16 * 256 * 16;
+constexpr int PART_BYTES = PART_O_BYTES + 256 * 8;
+constexpr int PART_COHERENT = 1 | 16;    // buffer cache policy sc0 | sc1: system scope, bypasses the XCD-local L2
 
 typedef __bf16 bf16x4_v __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2_v __attribute__((ext_vector_type(2)));
@@ -63,14 +68,23 @@ __device__ __forceinline__ float half_swap_max(float v) {
 // overlaps the matrix instructions of the other.  SKEW (with KVS = 2): the second group runs one phase behind the
 // first (its second product is deferred to the next iteration), so that the two waves of a SIMD, which leave every
 // barrier together, do not ask for the same pipe at the same time (measured 2-5 %).
+//
+// ksplit > 1 (gridDim.z = ksplit; launches of far fewer workgroups than the chip has compute units): the key tiles of
+// a row block are dealt to ksplit workgroups in contiguous shares (each share split again between the two wave groups).
+// Every workgroup parks its partial state (maximum, sum, unnormalised output) in its slot of `part_ws` with
+// cache-bypassing stores and then raises the row block's arrival counter; the workgroup that arrives last fetches all
+// ksplit states and folds them in share order -- the result does not depend on who arrived last -- normalises, writes
+// the rows and puts the counter back to zero for the next launch.  Nobody waits for anybody.
 template <int NSTAGE, int KVS, bool SKEW>
 __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_kernel(const bf16_t *__restrict__ Q,
                                                             const bf16_t *__restrict__ Kc,
                                                             const bf16_t *__restrict__ Vc,
                                                             bf16_t *__restrict__ Out, int Tc, int q_offset,
-                                                            int kv_len, int nq, int nkv, int q_stride, int pair) {
+                                                            int kv_len, int nq, int nkv, int q_stride, int pair,
+                                                            int ksplit, unsigned char *part_ws, unsigned *part_cnt) {
 #if defined(__HIP_DEVICE_COMPILE__)
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    __shared__ int last_arriver;
 
     const int tid = threadIdx.x, lane = tid & 63;
     // wave-uniform values are made scalar explicitly: LDS bases of the wave-loads, the diagonal tests and the mask
@@ -166,12 +180,16 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
     const float sc = 1.4426950408889634f / sqrtf((float)D);
 
     const int kv_end = min(kv_len, q_offset + min(m0 + BM, Tc));    // exclusive
-    const int n_tiles_all = (kv_end + BN - 1) / BN;
+    const int n_tiles_blk = (kv_end + BN - 1) / BN;                  // key tiles of the row block
+    // this workgroup's share [wg_lo, wg_lo + n_tiles_all) of them (all, unless the keys are split across workgroups)
+    const int share = (n_tiles_blk + ksplit - 1) / ksplit;
+    const int wg_lo = (int)blockIdx.z * share;
+    const int n_tiles_all = max(0, min(share, n_tiles_blk - wg_lo));
     // this group's tiles [t_lo, t_lo + n_tiles); with KVS == 2 the first group takes the larger half and both groups
     // run the loop n_iter times so that they meet at every barrier
     const int half = (n_tiles_all + KVS - 1) / KVS;
-    const int t_lo = kgrp * half;
-    const int n_tiles = max(0, min(half, n_tiles_all - t_lo));
+    const int t_lo = wg_lo + kgrp * half;
+    const int n_tiles = max(0, min(half, n_tiles_all - kgrp * half));
     // SKEW: the second group is one phase behind (see below) and needs one iteration more than it has tiles
     const int n_iter = KVS == 1 ? n_tiles : (SKEW ? max(half, n_tiles_all - half + 1) : half);
 
@@ -388,6 +406,7 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
             const float m_b = xm[t4], l_b = xm[256 + t4];
             const float m_new = fmaxf(m_run, m_b);
             const float fa = __builtin_amdgcn_exp2f((m_run - m_new) * sc), fb = __builtin_amdgcn_exp2f((m_b - m_new) * sc);
+            m_run = m_new;
             l_run = l_run * fa + l_b * fb;
 #pragma unroll
             for (int dt = 0; dt < D / 32; ++dt)
@@ -395,11 +414,73 @@ __global__ __launch_bounds__(256 * KVS, KVS == 1 ? 2 : 1) void attn_bf16_dtl_ker
                 for (int r = 0; r < 16; ++r) o[dt][r] = o[dt][r] * fa + xo[(dt * 16 + r) * 256 + t4] * fb;
         }
     }
+    bool writes_rows = true;                // workgroup-uniform
+    if (ksplit > 1) {
+        // park this workgroup's state, count the arrival, and let the last arriver fold all states in share order
+        const int t4 = tid & 255;
+        const int blk = tile_m * nq + h;
+        const __amdgpu_buffer_rsrc_t rs_part = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(part_ws + (size_t)blk * ksplit * PART_BYTES), 0, ksplit * PART_BYTES, 0x00020000);
+        if (kgrp == 0) {
+            const uint32_t slot = (uint32_t)blockIdx.z * PART_BYTES;
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    f32x4_t v = {o[dt][4 * r4], o[dt][4 * r4 + 1], o[dt][4 * r4 + 2], o[dt][4 * r4 + 3]};
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rs_part,
+                                                           slot + (uint32_t)(((dt * 4 + r4) * 256 + t4) * 16), 0,
+                                                           PART_COHERENT);
+                }
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(m_run), rs_part, slot + PART_O_BYTES + t4 * 8, 0,
+                                                  PART_COHERENT);
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(l_run), rs_part, slot + PART_O_BYTES + t4 * 8 + 4, 0,
+                                                  PART_COHERENT);
+        }
+        __builtin_amdgcn_s_waitcnt(0);      // my stores have reached memory ...
+        __syncthreads();                    // ... and so have everybody's, before the arrival is counted
+        if (tid == 0) {
+            const unsigned before =
+                __hip_atomic_fetch_add(&part_cnt[blk], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            last_arriver = before == (unsigned)(ksplit - 1);
+            if (last_arriver) __hip_atomic_store(&part_cnt[blk], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        __syncthreads();
+        writes_rows = last_arriver != 0;
+        if (writes_rows && kgrp == 0) {
+            m_run = -1e30f;
+            l_run = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+            for (int sp = 0; sp < ksplit; ++sp) {
+                const uint32_t slot = (uint32_t)sp * PART_BYTES;
+                f32x4_t po[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    po[v] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                            rs_part, slot + (uint32_t)((v * 256 + t4) * 16), 0, PART_COHERENT));
+                const float m_b = __uint_as_float(
+                    __builtin_amdgcn_raw_buffer_load_b32(rs_part, slot + PART_O_BYTES + t4 * 8, 0, PART_COHERENT));
+                const float l_b = __uint_as_float(
+                    __builtin_amdgcn_raw_buffer_load_b32(rs_part, slot + PART_O_BYTES + t4 * 8 + 4, 0, PART_COHERENT));
+                const float m_new = fmaxf(m_run, m_b);
+                const float fa = __builtin_amdgcn_exp2f((m_run - m_new) * sc), fb = __builtin_amdgcn_exp2f((m_b - m_new) * sc);
+                m_run = m_new;
+                l_run = l_run * fa + l_b * fb;
+#pragma unroll
+                for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[dt][r] = o[dt][r] * fa + po[dt * 4 + r / 4][r % 4] * fb;
+            }
+        }
+    }
     // --- normalise and store: lane holds column q = lcol, rows d = 32 dt + 8 (r/4) + 4 lgrp + r%4
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_tot;
     const int row = m0 + wave * 32 + lcol;
-    if (kgrp == 0 && row < Tc) {
+    if (writes_rows && kgrp == 0 && row < Tc) {
         bf16_t *op = Out + ((size_t)row * nq + h) * D;
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
@@ -423,8 +504,11 @@ bool iso_attn_bf16_dtl_supported(int d, int kv_len, int nkv) {
 
 // shape: 0 = chosen from the size; forced by tests and measurement: 1 = key split inside the workgroup, 2 = key split
 // and two row blocks per workgroup, 3 = one row block, two workgroups per compute unit.
+// ksplit_req: 0 = key split across workgroups chosen from the size, 1 = never, 2..4 = that many shares (forced by tests;
+// ignored when the workspace is missing or too small).
 hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v, void *out, int Tc, int q_offset,
-                                    int kv_len, int nq, int nkv, int d, int q_stride, int shape, hipStream_t s) {
+                                    int kv_len, int nq, int nkv, int d, int q_stride, int shape, int ksplit_req,
+                                    const iso_attn_ws *ws, hipStream_t s) {
     if (d != D) return hipErrorInvalidValue;
     static iso_dev_mask lds_allowed[2];
     if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(attn_bf16_dtl_kernel<2, 1, false>), 2 * STAGE_B, &lds_allowed[0]);
@@ -446,13 +530,31 @@ hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v,
     const long long rounds = (paired + ncu - 1) / ncu;
     const bool pair_ok = wgs >= 320 && wgs <= 2048 && (paired <= ncu || paired * 10 >= 9 * rounds * ncu);
     const int mode = shape >= 1 && shape <= 3 ? shape - 1 : (pair_ok ? 1 : wgs < 512 ? 0 : 2);
+    // Launches of at most half as many workgroups as the chip has compute units also split the keys ACROSS
+    // workgroups, into as many shares as fit the chip once (at most 4, and at least two key tiles per share and wave
+    // group on the longest row block): the serial chain of key tiles per workgroup, which is what such a launch takes,
+    // shrinks by that factor.
+    int ksplit = 1;
+    if (ws && ws->part && ws->cnt && wgs <= ws->max_blocks) {
+        if (ksplit_req >= 2) {
+            ksplit = ksplit_req;
+        } else if (ksplit_req == 0 && mode == 0 && wgs * 2 <= ncu) {
+            const int longest = (min(kv_len, q_offset + Tc) + BN - 1) / BN;      // key tiles of the last row block
+            ksplit = (int)min((long long)4, (long long)ncu / wgs);
+            while (ksplit > 1 && longest < 4 * ksplit) --ksplit;
+        }
+        if (wgs * ksplit > ws->max_slots) ksplit = 1;
+    }
     if (mode == 0 || mode == 1)
-        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2, true>), dim3(mode == 0 ? n_blocks : (n_blocks + 1) / 2, nq), dim3(512),
-                           2 * 2 * STAGE_B, s, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc,
-                           q_offset, kv_len, nq, nkv, q_stride, mode);
+        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 2, true>), dim3(mode == 0 ? n_blocks : (n_blocks + 1) / 2, nq, ksplit),
+                           dim3(512), 2 * 2 * STAGE_B, s, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                           (bf16_t *)out, Tc, q_offset, kv_len, nq, nkv, q_stride, mode, ksplit,
+                           ws ? ws->part : nullptr, ws ? ws->cnt : nullptr);
     else
-        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 1, false>), dim3(n_blocks, nq), dim3(256), 2 * STAGE_B, s,
+        hipLaunchKernelGGL((attn_bf16_dtl_kernel<2, 1, false>), dim3(n_blocks, nq, ksplit), dim3(256), 2 * STAGE_B, s,
                            (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)out, Tc, q_offset, kv_len, nq,
-                           nkv, q_stride, 0);
+                           nkv, q_stride, 0, ksplit, ws ? ws->part : nullptr, ws ? ws->cnt : nullptr);
     return hipGetLastError();
 }
+
+size_t iso_attn_part_bytes(void) { return PART_BYTES; }

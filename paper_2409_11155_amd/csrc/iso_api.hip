@@ -124,6 +124,13 @@ iso_sk_ws *sk_for(iso_ctx *ctx, hipStream_t s) {
     return nullptr;
 }
 
+// Key-split attention workspace for a launch on stream s: one per stream of the context's own, none for others.
+const iso_attn_ws *attn_ws_for(const iso_ctx *ctx, hipStream_t s) {
+    if (s == ctx->stream[0] && ctx->aws[0].part) return &ctx->aws[0];
+    if (s == ctx->stream[1] && ctx->aws[1].part) return &ctx->aws[1];
+    return nullptr;
+}
+
 // Row ranges of a GEMM cut into ctx->gemm_segments launches (Section 3.2: several launches per matrix product,
 // so that compute units given back by a finishing transfer are picked up at the next launch).  Segments are
 // multiples of 256 rows; a product with fewer than 256 rows per segment is not cut.
@@ -201,7 +208,7 @@ int attention(iso_ctx *ctx, const void *q, int q_stride, const void *kc, const v
     const bool mfma = c.dtype == ISO_BF16 && !(ctx->flags & ISO_FLAG_SIMPLE_ATTN);
     if (mfma && !(ctx->flags & ISO_FLAG_ATTN_STAGED) && iso_attn_bf16_dtl_supported(c.head_dim, kv_len, c.n_kv_heads))
         e = iso_launch_attn_bf16_dtl(q, kc, vc, out, Tc, q_offset, kv_len, c.n_q_heads, c.n_kv_heads, c.head_dim, q_stride,
-                                     (ctx->flags >> 12) & 3, s);
+                                     (ctx->flags >> 12) & 3, (ctx->flags >> 14) & 7, attn_ws_for(ctx, s), s);
     else if (mfma && iso_attn_bf16_mfma_supported(c.head_dim))
         e = iso_launch_attn_bf16_mfma(q, kc, vc, out, Tc, q_offset, kv_len, c.n_q_heads, c.n_kv_heads, c.head_dim, q_stride, s);
     else
@@ -617,6 +624,17 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
                      hip_ok(hipMemset(ctx->sk[i].base, 0, 4096), "hipMemset(stream-K flags)");
             }
             if (!ok) break;
+            // key-split attention workspaces: one per stream (both streams may run an attention launch at once)
+            constexpr int ATTN_SLOTS = 512, ATTN_BLOCKS = 512;
+            for (int i = 0; i < 2 && ok; ++i) {
+                ctx->aws[i].max_slots = ATTN_SLOTS;
+                ctx->aws[i].max_blocks = ATTN_BLOCKS;
+                ok = hip_ok(hipMalloc((void **)&ctx->aws[i].part, (size_t)ATTN_SLOTS * iso_attn_part_bytes()),
+                            "hipMalloc(attention partial states)") &&
+                     hip_ok(hipMalloc((void **)&ctx->aws[i].cnt, ATTN_BLOCKS * sizeof(unsigned)), "hipMalloc(attention counters)") &&
+                     hip_ok(hipMemset(ctx->aws[i].cnt, 0, ATTN_BLOCKS * sizeof(unsigned)), "hipMemset(attention counters)");
+            }
+            if (!ok) break;
             // the memsets ran on the null stream, which the library's non-blocking streams do not wait for
             if (!hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize")) break;
             // static workspace of iso_gemm_rowpar_static: address on this device, kernel attributes
@@ -677,8 +695,11 @@ int iso_destroy(iso_ctx *ctx) {
         if (ctx->xstream[k]) (void)hipStreamDestroy(ctx->xstream[k]);
     }
     if (ctx->sk[0].err) (void)hipHostFree(ctx->sk[0].err);
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
         if (ctx->sk[i].base) (void)hipFree(ctx->sk[i].base);
+        if (ctx->aws[i].part) (void)hipFree(ctx->aws[i].part);
+        if (ctx->aws[i].cnt) (void)hipFree(ctx->aws[i].cnt);
+    }
     if (ctx->host_sink) (void)hipHostFree(ctx->host_sink);
     if (ctx->rope_cos) (void)hipFree(ctx->rope_cos);
     if (ctx->rope_sin) (void)hipFree(ctx->rope_sin);

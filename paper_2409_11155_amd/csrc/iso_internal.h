@@ -25,6 +25,16 @@ struct iso_sk_ws {
     int num_wg;        // grid size = compute units of the device
 };
 
+// Workspace of the attention launches that split the keys of a row block across workgroups: partial states and one
+// arrival counter per (row block, head).  Counters are zero between launches (the last arriver resets its own).
+// Launches that share a workspace must be ordered (same stream); the context keeps one per stream of its own.
+struct iso_attn_ws {
+    unsigned char *part;   // device, max_slots * iso_attn_part_bytes()
+    unsigned *cnt;         // device, max_blocks words, zeroed at creation
+    int max_slots;         // (row block, head, share) triples a launch may use
+    int max_blocks;        // (row block, head) pairs a launch may use
+};
+
 struct iso_ctx {
     iso_cfg cfg;
     int device;
@@ -52,6 +62,7 @@ struct iso_ctx {
     int gemm_segments; // launches per projection GEMM along M (0 or 1: one launch)
     int sk_hold;       // set while a pass enqueues work for which stream-K is not to be picked
     iso_sk_ws sk[2];   // stream-K GEMM workspaces, one per caller stream (bf16 contexts only; base == null otherwise)
+    iso_attn_ws aws[2];// key-split attention workspaces, likewise
     void *host_sink;   // pinned, 2 * max_seq * hidden elements
     // optional per-launch timing (iso_timing_*): event pairs recorded around every launch, in its stream
     int timing;
@@ -104,7 +115,9 @@ hipError_t iso_launch_attn_bf16_mfma(const void *q, const void *k, const void *v
                                      int q_offset, int kv_len, int nq, int nkv, int d, int q_stride, hipStream_t s);
 bool iso_attn_bf16_mfma_supported(int d);
 hipError_t iso_launch_attn_bf16_dtl(const void *q, const void *k, const void *v, void *out, int Tc, int q_offset,
-                                    int kv_len, int nq, int nkv, int d, int q_stride, int shape, hipStream_t s);
+                                    int kv_len, int nq, int nkv, int d, int q_stride, int shape, int ksplit_req,
+                                    const iso_attn_ws *ws_or_null, hipStream_t s);
+size_t iso_attn_part_bytes(void);      // bytes of one partial state in an iso_attn_ws
 bool iso_attn_bf16_dtl_supported(int d, int kv_len, int nkv);
 
 // ---- small device helpers ----------------------------------------------------------------------

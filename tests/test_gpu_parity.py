@@ -188,7 +188,11 @@ ATTN_CASES = [
                                         ("bf16", 128, iso.ISO_FLAG_ATTN_STAGED),
                                         ("bf16", 128, iso.ISO_FLAG_SIMPLE_ATTN), ("bf16", 64, 0),
                                         # the three launch shapes of the direct-to-LDS kernel, forced (bits 12..13)
-                                        ("bf16", 128, 1 << 12), ("bf16", 128, 2 << 12), ("bf16", 128, 3 << 12)])
+                                        ("bf16", 128, 1 << 12), ("bf16", 128, 2 << 12), ("bf16", 128, 3 << 12),
+                                        # keys split across 2, 3 and 4 workgroups (bits 14..16), in each launch shape
+                                        ("bf16", 128, (1 << 12) | (2 << 14)), ("bf16", 128, (1 << 12) | (4 << 14)),
+                                        ("bf16", 128, (2 << 12) | (3 << 14)), ("bf16", 128, (3 << 12) | (2 << 14)),
+                                        ("bf16", 128, (3 << 12) | (4 << 14)), ("bf16", 128, 1 << 14)])
 @pytest.mark.parametrize("Tc,q_offset,kv_len,nq,nkv", ATTN_CASES)
 def test_attn_chunk(dt, d, flags, Tc, q_offset, kv_len, nq, nkv):
     q, k, v = iso_inputs.make_qkv_cache(Tc, kv_len, nq, nkv, d, seed=Tc + q_offset, dtype=dt)
@@ -199,6 +203,10 @@ def test_attn_chunk(dt, d, flags, Tc, q_offset, kv_len, nq, nkv):
         ctx.sync()
         ref = orc.attention_chunk(h64(q, dt), h64(k, dt), h64(v, dt), q_offset, kv_len).reshape(Tc, nq * d)
         tol = TOL_STEP[dt]
+        if flags >> 14:      # a launch that split the keys leaves its arrival counters at zero: run it once more
+            out.fill(0)
+            ctx.attn_chunk(dev(q, dt), dev(k, dt), dev(v, dt), out, Tc, q_offset, kv_len, ctx.stream0)
+            ctx.sync()
         if dt == "bf16" and d == 128 and flags != iso.ISO_FLAG_SIMPLE_ATTN:
             # the matrix-core kernel rounds the probabilities to bf16 before the second product:
             # |d out| <= 2^-9 * sum_j p_j |v_j| <= 2^-9 max|v|, on top of the 2^-8 output rounding
@@ -257,6 +265,38 @@ def test_attn_chunk_full_size_deep_in_a_128k_cache_sampled_rows(Tc, q_offset):
         worst = max(worst, err / tol)
         assert err <= tol, (i, err, tol)
     print(f"deep-cache attention: worst row at {worst:.2f} of its bound over {len(rows)} rows")
+
+
+@pytest.mark.parametrize("Tc,q_offset,nq,nkv", [(1024, 0, 13, 13), (1024, 1024, 13, 13), (2048, 2048, 8, 1),
+                                                 (1000, 1500, 6, 2)])
+def test_attn_chunk_small_launch_splits_keys_across_workgroups(Tc, q_offset, nq, nkv):
+    """Chunks of 1k-2k rows give about a hundred row-block workgroups on 256 compute units: the launch rule then
+    splits every row block's keys over several workgroups (chosen by itself here, not forced), each parks a partial
+    state and the last arriver folds them in share order.  All rows against the oracle, on both streams of the
+    context at once (each stream has its own workspace), and twice: the second launch finds the counters at zero and
+    must give the same bits as the first (the fold order is fixed, whoever arrives last)."""
+    dt, d, kv_len = "bf16", 128, q_offset + Tc
+    q, k, v = iso_inputs.make_qkv_cache(Tc, kv_len, nq, nkv, d, seed=Tc + nq, dtype=dt)
+    ref = orc.attention_chunk(h64(q, dt), h64(k, dt), h64(v, dt), q_offset, kv_len).reshape(Tc, nq * d)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    tol = 2.0 ** -9 * float(np.abs(h64(v, dt)).max()) / rms + 2.0 ** -8 + 1e-4
+    with make_ctx(256, nq, nkv, d, 64, dt, kv_len) as ctx:
+        qd, kd, vd = dev(q, dt), dev(k, dt), dev(v, dt)
+        outs = [iso.DeviceArray((Tc, nq * d), dt, fill_byte=NAN_BYTE) for _ in range(4)]
+        for i, o in enumerate(outs):
+            ctx.attn_chunk(qd, kd, vd, o, Tc, q_offset, kv_len, ctx.stream0 if i % 2 == 0 else ctx.stream1)
+        ctx.sync()
+        first = outs[0].numpy()
+        err = orc.max_rel_err(h64(first, dt), ref)
+        assert err <= tol, (err, tol)
+        for o in outs[1:]:
+            np.testing.assert_array_equal(o.numpy(), first)
+        # the same launch with the split switched off agrees within the bound as well (other sum order)
+        ctx.set_flags(1 << 14)
+        plain = iso.DeviceArray((Tc, nq * d), dt, fill_byte=NAN_BYTE)
+        ctx.attn_chunk(qd, kd, vd, plain, Tc, q_offset, kv_len, ctx.stream0)
+        ctx.sync()
+        assert orc.max_rel_err(f64(plain), ref) <= tol
 
 
 def test_attn_chunk_rejects_bad_arguments():
