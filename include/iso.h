@@ -239,7 +239,8 @@ enum {
     ISO_FLAG_SIMPLE_GEMM = 1, /* SIMT tile GEMM instead of the MFMA GEMMs                  */
     ISO_FLAG_SIMPLE_ATTN = 2, /* one-wave-per-row attention instead of the MFMA attention  */
     ISO_FLAG_GEMM_STAGED = 4, /* register-staged 128x128 MFMA GEMM instead of the direct-to-LDS one */
-    ISO_FLAG_NO_FUSE = 8,     /* gate/up projection and SwiGLU as two kernels instead of one        */
+    ISO_FLAG_NO_FUSE = 8,     /* no fused epilogues: gate/up projection and SwiGLU as two kernels, QKV projection
+                                 and rotary embedding + KV-cache write as two kernels                  */
     ISO_FLAG_ATTN_STAGED = 16,/* register-staged MFMA attention instead of the direct-to-LDS one    */
     ISO_FLAG_NO_STREAMK = 32, /* never pick the stream-K launch of the direct-to-LDS GEMM by itself  */
     ISO_FLAG_FP8_GEMM = 64    /* bf16 layers: run the four projections on the FP8 matrix cores (needs the FP8

@@ -81,13 +81,28 @@ template <int BM, int BN, int WM, int WN> struct DtlCfg {
 // workgroups whose own waits point at workgroups dispatched before them.  Every wait is bounded as well: one that
 // exceeds the spin limit raises *sk_err (a pinned host word that the library reads at its next entry point and in
 // iso_sync) and carries on with a wrong tile.
-template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE, bool SK, bool M16 = false>
+//
+// ROPE = true (the QKV projection of a layer with head_dim 128; W = [q heads | k heads | v heads] x 128 rows): the
+// epilogue finishes the step that follows the projection (rotary embedding and KV-cache write, what the next chunk's
+// attention waits for, paper Section 3.1).  A wave's 128 output columns are exactly one head, and the rotation pairs
+// (c, c + 64) of a row are both in the wave's staging area, so q and k heads are rotated at position q_offset + row
+// on their way from the staging area to memory (same arithmetic and roundings as the separate rotary kernel: the
+// bf16 projection output is rotated in fp32 and rounded again), q heads go to C, k and v heads straight to rows
+// q_offset + row of the caches; the k/v columns of C are not written.
+struct RopeArgs {
+    const float *cos_t, *sin_t;      // [max_seq, 64] fp32 tables
+    bf16_t *k_cache, *v_cache;       // [max_seq, nkv, 128]
+    int q_offset, nq, nkv;
+};
+
+template <int BM, int BN, int WM, int WN, bool SWIGLU, bool PIPE, bool SK, bool M16 = false, bool ROPE = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_t *__restrict__ A,
                                                                      const bf16_t *__restrict__ W,
                                                                      bf16_t *__restrict__ C, int M, int N, int K,
                                                                      int tiles_m, int tiles_n,
                                                                      unsigned char *sk_ws, unsigned sk_epoch,
-                                                                     unsigned *sk_err, int sk_team, int sk_grouped) {
+                                                                     unsigned *sk_err, int sk_team, int sk_grouped,
+                                                                     RopeArgs rope) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource builtins exist in the device pass only
     using Cfg = DtlCfg<BM, BN, WM, WN>;
     constexpr int NWAVES = Cfg::NWAVES, A_BYTES = Cfg::A_BYTES, STAGE = Cfg::STAGE;
@@ -334,6 +349,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
     auto store_tile = [&]() {
         __syncthreads();                         // every wave is done reading operand tiles
         if (!SWIGLU) {
+            const int gm0 = m0 + wm * Cfg::WTM, gn0 = n0 + wn * Cfg::WTN;
+            // where this wave's columns go: C, or (ROPE) the head's place in a cache row
+            bf16_t *dst = C + gn0;
+            size_t dst_stride = (size_t)N;
+            int dst_row0 = gm0;
+            bool rotate = false;                                 // wave-uniform
+            if constexpr (ROPE) {
+                static_assert(Cfg::WTN == 128 && TN == 4, "a wave's columns are one head of 128");
+                const int head = gn0 / 128;                      // wave-uniform
+                rotate = head < rope.nq + rope.nkv;              // q and k heads
+                if (head >= rope.nq) {                           // k or v head: rows q_offset + m of its cache
+                    const bool is_k = head < rope.nq + rope.nkv;
+                    dst = (is_k ? rope.k_cache : rope.v_cache) + (size_t)(head - rope.nq - (is_k ? 0 : rope.nkv)) * 128;
+                    dst_stride = (size_t)rope.nkv * 128;
+                    dst_row0 = rope.q_offset + gm0;
+                }
+            }
             bf16_t *ct = reinterpret_cast<bf16_t *>(lds) + (size_t)wave * Cfg::WTM * Cfg::CP;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -347,15 +379,49 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_dtl_kernel(const bf16_
             constexpr int CPR = Cfg::WTN / 8;        // 16-byte pieces per row
             constexpr int PIECES = Cfg::WTM * CPR;
             static_assert(PIECES % 64 == 0, "whole wave-stores");
-            const int gm0 = m0 + wm * Cfg::WTM, gn0 = n0 + wn * Cfg::WTN;
+            if (ROPE && rotate) {
+                // rotary embedding on the way out: a lane takes the 16-byte piece at columns cc .. cc + 7 (cc < 64) of
+                // a row together with its partner at cc + 64, the row's cos / sin for those eight pairs as four
+                // 16-byte loads, and writes both rotated pieces (the accumulators are no longer live here, so the
+                // table loads of several pieces can be in flight at once)
+                constexpr int HPR = CPR / 2;         // piece pairs per row
 #pragma unroll
-            for (int it = 0; it < PIECES / 64; ++it) {
-                const int p = lane + it * 64;
-                const int row = p / CPR, cc = (p % CPR) * 8;
-                const int gm = gm0 + row, gn = gn0 + cc;
-                if (gm < M && gn < N)                // N % 8 == 0: a piece is entirely inside or outside
-                    *reinterpret_cast<uint4 *>(C + (size_t)gm * N + gn) =
-                        *reinterpret_cast<const uint4 *>(ct + row * Cfg::CP + cc);
+                for (int it = 0; it < PIECES / 128; ++it) {
+                    const int p = lane + it * 64;
+                    const int row = p / HPR, cc = (p % HPR) * 8;
+                    const int gm = gm0 + row;
+                    if (gm < M && gn0 < N) {         // a head is entirely inside or outside the matrix
+                        const size_t t = (size_t)(rope.q_offset + gm) * 64 + cc;
+                        const float4 c0 = *reinterpret_cast<const float4 *>(rope.cos_t + t);
+                        const float4 c1 = *reinterpret_cast<const float4 *>(rope.cos_t + t + 4);
+                        const float4 s0 = *reinterpret_cast<const float4 *>(rope.sin_t + t);
+                        const float4 s1 = *reinterpret_cast<const float4 *>(rope.sin_t + t + 4);
+                        const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+                        const float sn[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+                        const bf16x8_t lo = *reinterpret_cast<const bf16x8_t *>(ct + row * Cfg::CP + cc);
+                        const bf16x8_t hi = *reinterpret_cast<const bf16x8_t *>(ct + row * Cfg::CP + cc + 64);
+                        bf16x8_t olo, ohi;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float l = (float)lo[e], h = (float)hi[e];
+                            olo[e] = (bf16_t)(l * cs[e] - h * sn[e]);
+                            ohi[e] = (bf16_t)(h * cs[e] + l * sn[e]);
+                        }
+                        bf16_t *o = dst + (size_t)(dst_row0 + row) * dst_stride + cc;
+                        *reinterpret_cast<bf16x8_t *>(o) = olo;
+                        *reinterpret_cast<bf16x8_t *>(o + 64) = ohi;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int it = 0; it < PIECES / 64; ++it) {
+                    const int p = lane + it * 64;
+                    const int row = p / CPR, cc = (p % CPR) * 8;
+                    const int gm = gm0 + row, gn = gn0 + cc;
+                    if (gm < M && gn < N)            // N % 8 == 0: a piece is entirely inside or outside
+                        *reinterpret_cast<uint4 *>(dst + (size_t)(dst_row0 + row) * dst_stride + cc) =
+                            *reinterpret_cast<const uint4 *>(ct + row * Cfg::CP + cc);
+                }
             }
         } else {
             constexpr int HW = Cfg::WTN / 2;         // output columns per wave
@@ -532,7 +598,7 @@ hipError_t launch(const void *a, const void *w, void *c, int M, int N, int K, hi
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     dim3 grid(tiles_m * tiles_n), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
-                       K, tiles_m, tiles_n, (unsigned char *)nullptr, 0u, (unsigned *)nullptr, 1, 0);
+                       K, tiles_m, tiles_n, (unsigned char *)nullptr, 0u, (unsigned *)nullptr, 1, 0, RopeArgs{});
     return hipGetLastError();
 }
 
@@ -556,7 +622,7 @@ hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K,
     ++sk->epoch;
     dim3 grid(G), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
-                       K, tiles_m, tiles_n, (unsigned char *)sk->base, sk->epoch, sk->err, TS, grouped);
+                       K, tiles_m, tiles_n, (unsigned char *)sk->base, sk->epoch, sk->err, TS, grouped, RopeArgs{});
     return hipGetLastError();
 }
 
@@ -616,7 +682,7 @@ hipError_t iso_launch_gemm_bf16_sk_static(const void *a, const void *w, void *c,
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, false, true, true>;
     hipLaunchKernelGGL(kern, dim3(G), dim3(Cfg::NT), LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
-                       K, tiles_m, tiles_n, ptr, 1u, err_word, TS, grouped);
+                       K, tiles_m, tiles_n, ptr, 1u, err_word, TS, grouped, RopeArgs{});
     return hipGetLastError();
 }
 
@@ -723,6 +789,49 @@ hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M
         default: ISO_DTL(128, 128, 2, 2);
     }
 #undef ISO_DTL
+}
+
+// The kernel variant a launch with `variant` (0 = pick by shape) resolves to, without launching.
+int iso_gemm_bf16_dtl_resolve(int M, int N, int K, int variant, const iso_sk_ws *sk) {
+    int v = variant & 7;
+    if (v == 0) v = sk_wanted(M, N, K, sk) ? 6 : pick_variant(M, N);
+    if (v == 6 && !(sk && sk->base)) v = -1;
+    return ((variant >> 3) & 1) ? v + 8 : v;
+}
+
+// QKV projection with rotary embedding and KV-cache write in its epilogue (head_dim 128).  Only the variants whose
+// waves own 128 output columns take it: `resolved` must be 1 (256x256 tile per workgroup) or 6 (its stream-K launch),
+// as given by iso_gemm_bf16_dtl_resolve; anything else is hipErrorInvalidValue and the caller runs the plain
+// projection followed by the separate rotary kernel.
+hipError_t iso_launch_gemm_qkv_rope_bf16(const void *a, const void *w, void *qkv, int M, int N, int K, int resolved,
+                                         iso_sk_ws *sk, const float *cos_t, const float *sin_t, void *k_cache,
+                                         void *v_cache, int q_offset, int nq, int nkv, hipStream_t s) {
+    if (N != (nq + 2 * nkv) * 128 || (resolved != 1 && resolved != 6)) return hipErrorInvalidValue;
+    using Cfg = DtlCfg<256, 256, 4, 2>;
+    constexpr int LDS_BYTES = Cfg::W3 ? Cfg::LDS_BYTES_W3 : Cfg::LDS_BYTES;
+    const RopeArgs rope{cos_t, sin_t, (bf16_t *)k_cache, (bf16_t *)v_cache, q_offset, nq, nkv};
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    if (resolved == 1) {
+        static iso_dev_mask lds_allowed{0};
+        auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, false, true, false, true, true>;
+        if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), LDS_BYTES, &lds_allowed); e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(Cfg::NT), LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w,
+                           (bf16_t *)qkv, M, N, K, tiles_m, tiles_n, (unsigned char *)nullptr, 0u, (unsigned *)nullptr, 1, 0,
+                           rope);
+        return hipGetLastError();
+    }
+    if (!(sk && sk->base)) return hipErrorInvalidValue;
+    static iso_dev_mask lds_allowed_sk{0};
+    auto kern = gemm_bf16_dtl_kernel<256, 256, 4, 2, false, true, true, false, true>;
+    if (hipError_t e = iso_allow_lds(reinterpret_cast<const void *>(kern), LDS_BYTES, &lds_allowed_sk); e != hipSuccess)
+        return e;
+    int TS, G, grouped;
+    sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped);
+    ++sk->epoch;
+    hipLaunchKernelGGL(kern, dim3(G), dim3(Cfg::NT), LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)qkv, M, N,
+                       K, tiles_m, tiles_n, (unsigned char *)sk->base, sk->epoch, sk->err, TS, grouped, rope);
+    return hipGetLastError();
 }
 
 // act[M, F] = silu(a w_gate^T) * (a w_up^T) with w = [gate; up] of shape [2F, K].

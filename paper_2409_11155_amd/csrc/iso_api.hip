@@ -125,10 +125,23 @@ iso_sk_ws *sk_for(iso_ctx *ctx, hipStream_t s) {
 }
 
 // Key-split attention workspace for a launch on stream s: one per stream of the context's own, none for others.
+constexpr int ATTN_SLOTS = 512, ATTN_BLOCKS = 512;
+
 const iso_attn_ws *attn_ws_for(const iso_ctx *ctx, hipStream_t s) {
     if (s == ctx->stream[0] && ctx->aws[0].part) return &ctx->aws[0];
     if (s == ctx->stream[1] && ctx->aws[1].part) return &ctx->aws[1];
+    for (int k = 2; k < ISO_MAX_CHUNKS; ++k)
+        if (ctx->xstream[k] && s == ctx->xstream[k] && ctx->aws[k].part) return &ctx->aws[k];
     return nullptr;
+}
+
+// Allocates one key-split attention workspace (counters zeroed; the caller synchronises the device afterwards).
+hipError_t attn_ws_create(iso_attn_ws *ws) {
+    ws->max_slots = ATTN_SLOTS;
+    ws->max_blocks = ATTN_BLOCKS;
+    if (hipError_t e = hipMalloc((void **)&ws->part, (size_t)ATTN_SLOTS * iso_attn_part_bytes()); e != hipSuccess) return e;
+    if (hipError_t e = hipMalloc((void **)&ws->cnt, ATTN_BLOCKS * sizeof(unsigned)); e != hipSuccess) return e;
+    return hipMemset(ws->cnt, 0, ATTN_BLOCKS * sizeof(unsigned));
 }
 
 // Row ranges of a GEMM cut into ctx->gemm_segments launches (Section 3.2: several launches per matrix product,
@@ -289,6 +302,32 @@ int attn_block_head(iso_ctx *ctx, const iso_weights *w, void *x, void *kc, void 
     } else {
         LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, nullptr, nullptr, w->g_attn, yr, ck.n, H, c.rms_eps, 0, 0, ck.s), "rmsnorm");
     }
+    // bf16 layers with head_dim 128: rotary embedding and KV-cache write ride in the projection's epilogue whenever
+    // the launch rule picks a kernel whose waves own whole heads (the 256-wide tile or its stream-K launch)
+    const bool dtl = c.dtype == ISO_BF16 && c.head_dim == 128 && !use_fp8(ctx, f8, ck.n, NQKV, H) &&
+                     !(ctx->flags & (ISO_FLAG_SIMPLE_GEMM | ISO_FLAG_GEMM_STAGED | ISO_FLAG_NO_FUSE)) &&
+                     iso_gemm_bf16_dtl_supported(ck.n, NQKV, H);
+    if (dtl) {
+        const int segs = (ctx->gemm_segments > 1 && ck.n >= 256 * ctx->gemm_segments) ? ctx->gemm_segments : 1;
+        const int per = ((ck.n + segs - 1) / segs + 255) / 256 * 256;
+        bool all_fusable = true;                    // every segment must resolve to a head-owning variant
+        for (int lo = 0; lo < ck.n; lo += per) {
+            const int v = iso_gemm_bf16_dtl_resolve(std::min(per, ck.n - lo), NQKV, H, (ctx->flags >> 8) & 15, sk_for(ctx, ck.s));
+            all_fusable = all_fusable && (v == 1 || v == 6);
+        }
+        if (all_fusable) {
+            Timed t_(ctx, ISO_K_GEMM_QKV, ck.s);
+            return for_segments(ctx, ck.n, [&](int lo, int n) {
+                iso_sk_ws *sk = sk_for(ctx, ck.s);
+                const int v = iso_gemm_bf16_dtl_resolve(n, NQKV, H, (ctx->flags >> 8) & 15, sk);
+                hipError_t e_ = iso_launch_gemm_qkv_rope_bf16(yr + (size_t)lo * H * e, w->w_qkv, qkvr + (size_t)lo * NQKV * e, n,
+                                                              NQKV, H, v, sk, ctx->rope_cos, ctx->rope_sin, kc, vc, ck.lo + lo,
+                                                              c.n_q_heads, c.n_kv_heads, ck.s);
+                if (e_ != hipSuccess) return fail(ISO_ERR_HIP, "qkv+rope launch: %s", hipGetErrorString(e_));
+                return (int)ISO_OK;
+            });
+        }
+    }
     ISO_TRY(gemm(ctx, ISO_K_GEMM_QKV, yr, w->w_qkv, qkvr, ck.n, NQKV, H, ck.s, f8));
     LAUNCH_TRY(ISO_K_ROPE_KV, ck.s, iso_launch_rope_kv(c.dtype, qkvr, kc, vc, ctx->rope_cos, ctx->rope_sin, ck.n, ck.lo, c.n_q_heads,
                                   c.n_kv_heads, c.head_dim, ck.s), "rope+kv");
@@ -395,7 +434,13 @@ int chunk_streams(iso_ctx *ctx, int nc, hipStream_t *out) {
     out[0] = ctx->stream[0];
     out[1] = ctx->stream[1];
     for (int k = 2; k < nc; ++k) {
-        if (!ctx->xstream[k]) HIP_TRY(hipStreamCreateWithFlags(&ctx->xstream[k], hipStreamNonBlocking));
+        if (!ctx->xstream[k]) {
+            HIP_TRY(hipStreamCreateWithFlags(&ctx->xstream[k], hipStreamNonBlocking));
+            if (ctx->cfg.dtype == ISO_BF16 && !ctx->aws[k].part) {   // same launch choices as on the caller's streams
+                HIP_TRY(attn_ws_create(&ctx->aws[k]));
+                HIP_TRY(hipDeviceSynchronize());
+            }
+        }
         out[k] = ctx->xstream[k];
     }
     return ISO_OK;
@@ -625,15 +670,7 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
             }
             if (!ok) break;
             // key-split attention workspaces: one per stream (both streams may run an attention launch at once)
-            constexpr int ATTN_SLOTS = 512, ATTN_BLOCKS = 512;
-            for (int i = 0; i < 2 && ok; ++i) {
-                ctx->aws[i].max_slots = ATTN_SLOTS;
-                ctx->aws[i].max_blocks = ATTN_BLOCKS;
-                ok = hip_ok(hipMalloc((void **)&ctx->aws[i].part, (size_t)ATTN_SLOTS * iso_attn_part_bytes()),
-                            "hipMalloc(attention partial states)") &&
-                     hip_ok(hipMalloc((void **)&ctx->aws[i].cnt, ATTN_BLOCKS * sizeof(unsigned)), "hipMalloc(attention counters)") &&
-                     hip_ok(hipMemset(ctx->aws[i].cnt, 0, ATTN_BLOCKS * sizeof(unsigned)), "hipMemset(attention counters)");
-            }
+            for (int i = 0; i < 2 && ok; ++i) ok = hip_ok(attn_ws_create(&ctx->aws[i]), "attention key-split workspace");
             if (!ok) break;
             // the memsets ran on the null stream, which the library's non-blocking streams do not wait for
             if (!hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize")) break;
@@ -695,8 +732,9 @@ int iso_destroy(iso_ctx *ctx) {
         if (ctx->xstream[k]) (void)hipStreamDestroy(ctx->xstream[k]);
     }
     if (ctx->sk[0].err) (void)hipHostFree(ctx->sk[0].err);
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 2; ++i)
         if (ctx->sk[i].base) (void)hipFree(ctx->sk[i].base);
+    for (int i = 0; i < ISO_MAX_CHUNKS; ++i) {
         if (ctx->aws[i].part) (void)hipFree(ctx->aws[i].part);
         if (ctx->aws[i].cnt) (void)hipFree(ctx->aws[i].cnt);
     }

@@ -62,7 +62,7 @@ struct iso_ctx {
     int gemm_segments; // launches per projection GEMM along M (0 or 1: one launch)
     int sk_hold;       // set while a pass enqueues work for which stream-K is not to be picked
     iso_sk_ws sk[2];   // stream-K GEMM workspaces, one per caller stream (bf16 contexts only; base == null otherwise)
-    iso_attn_ws aws[2];// key-split attention workspaces, likewise
+    iso_attn_ws aws[ISO_MAX_CHUNKS];   // key-split attention workspaces: [0], [1] for the caller's streams, [k] for xstream[k]
     void *host_sink;   // pinned, 2 * max_seq * hidden elements
     // optional per-launch timing (iso_timing_*): event pairs recorded around every launch, in its stream
     int timing;
@@ -87,6 +87,12 @@ bool iso_gemm_bf16_mfma_supported(int M, int N, int K);
 hipError_t iso_launch_gemm_bf16_dtl(const void *a, const void *w, void *c, int M, int N, int K, int variant,
                                     iso_sk_ws *sk_or_null, hipStream_t s);
 bool iso_gemm_bf16_dtl_supported(int M, int N, int K);
+// which variant (1..6; -1: none; +8: plain main loop) a launch with `variant` resolves to
+int iso_gemm_bf16_dtl_resolve(int M, int N, int K, int variant, const iso_sk_ws *sk_or_null);
+// QKV projection with rotary embedding + KV-cache write in the epilogue (head_dim 128; resolved variant 1 or 6)
+hipError_t iso_launch_gemm_qkv_rope_bf16(const void *a, const void *w, void *qkv, int M, int N, int K, int resolved,
+                                         iso_sk_ws *sk_or_null, const float *cos_t, const float *sin_t, void *k_cache,
+                                         void *v_cache, int q_offset, int nq, int nkv, hipStream_t s);
 hipError_t iso_launch_gemm_swiglu_bf16(const void *a, const void *w, void *act, int M, int F, int K, int variant,
                                        iso_sk_ws *sk_or_null, hipStream_t s);
 void iso_gemm_bf16_dtl_plan(int M, int N, int K, int num_wg, int *kind, int *team, int *grid);

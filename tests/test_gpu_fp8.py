@@ -146,6 +146,57 @@ def test_full_size_30b_tp4_2k_fp8_projections_sampled_rows():
             assert rms_rel_err(f64(kc), ref["k_cache"]) <= TOL_RMS_FP8
 
 
+def test_full_size_30b_tp4_2k_fp8_projection_from_the_devices_own_intermediate():
+    """The layer bounds above are statistical (device and oracle quantise activations that differ by bf16 roundings),
+    so a single wrong element could hide under them.  Here the oracle is fed the DEVICE's own bf16 intermediate: the
+    norm output y of the full 30B TP=4 prompt is downloaded, the oracle quantises exactly those values and the
+    weights (its quantiser is bit-identical to the device's), and every element of the device's FP8 QKV projection
+    (2048 x 4992 x 6656, through the fused norm + quantiser as the layer runs it, and through the separate quantiser)
+    must match the oracle's product at the single-step bound.  Then the same for o_proj fed the device's attention
+    output."""
+    wl = iso_inputs.WORKLOADS["30b_tp4_2k"]
+    dt, T, H = wl.dtype, wl.seq, wl.hidden
+    nqd = wl.n_q_heads * wl.head_dim
+    x, w = iso_inputs.make_workload_inputs(wl, seed=0)
+    with make_ctx(H, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, T) as ctx:
+        s = ctx.stream0
+        wd = ctx.add_fp8_weights(iso.upload_weights(w, dt))
+        xd = dev(x, dt)
+        y = iso.DeviceArray((T, H), dt)
+        ctx.rmsnorm(xd, wd["g_attn"], y, T, s)
+        a8, sa = iso.DeviceArray((T, H), "u8"), iso.DeviceArray((T,), "f32")
+        ctx.rmsnorm_fp8(xd, None, wd["g_attn"], a8, sa, T, s)         # what the layer does under ISO_FLAG_FP8_GEMM
+        qkv = iso.DeviceArray((T, wl.n_qkv), dt, fill_byte=NAN_BYTE)
+        ctx.gemm_fp8(a8, sa, wd["w_qkv_f8"], wd["s_qkv"], qkv, T, wl.n_qkv, H, s)
+        b8, sb = iso.DeviceArray((T, H), "u8"), iso.DeviceArray((T,), "f32")
+        ctx.quantize_rows_fp8(y, T, H, b8, sb, s)                     # the separate quantiser on the stored y
+        qkv2 = iso.DeviceArray((T, wl.n_qkv), dt, fill_byte=NAN_BYTE)
+        ctx.gemm_fp8(b8, sb, wd["w_qkv_f8"], wd["s_qkv"], qkv2, T, wl.n_qkv, H, s)
+        ctx.sync()
+        ref = orc.linear_fp8(f64(y), h64(w["w_qkv"], dt))
+        err = orc.max_rel_err(f64(qkv), ref)
+        print("fp8 QKV from the device's own y: max_rel_err", err)
+        assert err <= TOL_STEP[dt], err
+        np.testing.assert_array_equal(qkv2.numpy(), qkv.numpy())
+        # o_proj on the device's own attention output (bf16 layer run first to produce it through the library)
+        kc = iso.DeviceArray((T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=0)
+        vc = iso.DeviceArray((T, wl.n_kv_heads, wl.head_dim), dt, fill_byte=0)
+        ctx.rope_kv_write(qkv, kc, vc, T, 0, s)
+        ctx.sync()
+        q_only = dev(np.ascontiguousarray(qkv.numpy()[:, :nqd]), dt)
+        att = iso.DeviceArray((T, nqd), dt)
+        ctx.attn_chunk(q_only, kc, vc, att, T, 0, T, s)
+        o8, so = iso.DeviceArray((T, nqd), "u8"), iso.DeviceArray((T,), "f32")
+        ctx.quantize_rows_fp8(att, T, nqd, o8, so, s)
+        pa = iso.DeviceArray((T, H), dt, fill_byte=NAN_BYTE)
+        ctx.gemm_fp8(o8, so, wd["w_o_f8"], wd["s_o"], pa, T, H, nqd, s)
+        ctx.sync()
+        ref_o = orc.linear_fp8(f64(att), h64(w["w_o"], dt))
+        err_o = orc.max_rel_err(f64(pa), ref_o)
+        print("fp8 o_proj from the device's own attention output: max_rel_err", err_o)
+        assert err_o <= TOL_STEP[dt], err_o
+
+
 @pytest.mark.parametrize("hidden", [256, 6656, 8192])
 @pytest.mark.parametrize("with_delta", [False, True])
 def test_norm_with_fp8_tail_equals_norm_then_quantiser(hidden, with_delta):

@@ -396,6 +396,42 @@ def test_small_bf16_layer_all_rows(flags, hidden, nq, nkv, ffn, T, splits):
             assert orc.max_rel_err(f64(vc)[:T], ref["v_cache"]) <= TOL_LAYER["bf16"]
 
 
+@pytest.mark.parametrize("variant", [1 << 8, 6 << 8, 0])
+@pytest.mark.parametrize("hidden,nq,nkv,T,split", [(512, 4, 1, 300, 130), (384, 3, 3, 700, 257), (1024, 8, 2, 1100, 0)])
+def test_rotary_and_cache_write_in_the_qkv_epilogue_against_the_separate_kernel(variant, hidden, nq, nkv, T, split):
+    """bf16 layers with head_dim 128 rotate q/k and write the caches in the epilogue of the QKV projection (256-wide
+    tile, forced here as variant 1, and its stream-K launch, variant 6; 0 = the launch rule's own choice).  Against
+    the same layer with the separate rotary kernel (ISO_FLAG_NO_FUSE): V rows are copies of the same bf16
+    projection output and must be the same bits; K rows and the layer output go through the same roundings (bf16
+    projection output, rotation in fp32, bf16) and must both match the oracle, the fused K as closely as the other."""
+    d, dt, ffn = 128, "bf16", 512
+    w = iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=23, dtype=dt)
+    x = iso_inputs.make_hidden(T, hidden, seed=23, dtype=dt)
+    ref = orc.layer_unsplit(h64(x, dt), oracle_weights(w, dt), shape_of(hidden, nq, nkv, d, ffn))
+    w_dev = iso.upload_weights(w, dt)
+    max_seq = T + 37                                   # rows past the prompt must stay untouched
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, max_seq) as ctx:
+        got = {}
+        for name, flags in (("fused", variant), ("separate", variant | iso.ISO_FLAG_NO_FUSE)):
+            ctx.set_flags(flags)
+            ctx.timing_enable(True)
+            out, kc, vc = run_layer(ctx, w_dev, x, dt, T, split, nkv, d, max_seq, iso.ISO_COMM_D2H, poison=True)
+            n_rope = ctx.timing_read()["rope_kv"][1]
+            ctx.timing_enable(False)
+            got[name] = (f64(out), f64(kc), vc.numpy(), n_rope)
+            assert orc.max_rel_err(got[name][0], ref["x_out"]) <= TOL_LAYER[dt], name
+            assert orc.max_rel_err(got[name][1][:T], ref["k_cache"]) <= TOL_LAYER[dt], name
+            assert np.isnan(got[name][1][T:]).all(), name
+        n_chunks = 2 if 0 < split < T else 1
+        assert got["separate"][3] == n_chunks
+        if variant:                                    # forced onto a head-owning kernel: no rotary launch left
+            assert got["fused"][3] == 0
+        np.testing.assert_array_equal(got["fused"][2], got["separate"][2])
+        rms_f = np.sqrt(np.mean((got["fused"][1][:T] - ref["k_cache"]) ** 2))
+        rms_s = np.sqrt(np.mean((got["separate"][1][:T] - ref["k_cache"]) ** 2))
+        assert rms_f <= rms_s * 1.02, (rms_f, rms_s)
+
+
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_degenerate_prompts_of_one_two_and_three_tokens(dt):
     """The shortest prompts: a single token attends to itself only; with two or three tokens every cut leaves
