@@ -71,3 +71,35 @@ def test_static_workspace_gemm_rejects_what_it_cannot_take():
         with pytest.raises(iso.IsoError) as ei:
             c32.gemm_rowpar_static(t, t, t, 64, 64, 64, c32.stream0)
         assert ei.value.code == iso.ISO_ERR_DTYPE
+
+
+def test_static_workspace_gemm_recorded_into_a_graph_and_replayed():
+    """What the entry point is for: a caller that records its work into a HIP graph.  The call is captured once (two
+    kernel nodes, no memset node, no allocation) and replayed with changing contents of `a`, with eager work and a
+    synchronisation between the replays; every replay must give the bits of the eager call on the same operands."""
+    from test_gpu_graph import Captured, hip_runtime
+    rt = hip_runtime()
+    dt, (M, N, K) = "bf16", (1024, 2304, 4096)
+    w = iso_inputs.randn((N, K), seed=71, dtype=dt, scale=K ** -0.5)
+    a_sets = [iso_inputs.randn((M, K), seed=72 + i, dtype=dt) for i in range(3)]
+    with iso.Context(iso.make_cfg(256, 4, 4, 64, 64, dt, 256)) as ctx:
+        wd = iso.DeviceArray.from_numpy(w, dt)
+        ad = iso.DeviceArray.from_numpy(a_sets[0], dt)
+        cd = iso.DeviceArray((M, N), dt, fill_byte=NAN_BYTE)
+        eager = iso.DeviceArray((M, N), dt, fill_byte=NAN_BYTE)
+        ctx.gemm_rowpar_static(ad, wd, cd, M, N, K, ctx.stream0)          # once eagerly, as for every captured call
+        ctx.sync()
+        g = Captured(rt, ctx.stream0.handle, lambda: ctx.gemm_rowpar_static(ad, wd, cd, M, N, K, ctx.stream0))
+        try:
+            for a in a_sets + a_sets[:1]:
+                ad.upload(a)                                              # synchronous copy: eager work between replays
+                cd.fill(NAN_BYTE)
+                ctx.gemm_rowpar_static(ad, wd, eager, M, N, K, ctx.stream0)
+                ctx.sync()
+                g.launch()
+                ctx.sync()
+                got = cd.numpy()
+                np.testing.assert_array_equal(got, eager.numpy())
+                assert orc.max_rel_err(h64(got), orc.linear(h64(a), h64(w))) <= TOL_STEP_BF16
+        finally:
+            g.destroy()
