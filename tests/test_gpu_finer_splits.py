@@ -88,10 +88,12 @@ def test_schedules_agree_bit_for_bit_and_never_read_an_unwritten_cache_row():
                 np.testing.assert_array_equal(bits, first)
 
 
-@pytest.mark.parametrize("n_chunks,sched", [(4, iso.ISO_SCHED_OVERLAP), (4, iso.ISO_SCHED_STREAM_PER_CHUNK),
-                                            (3, iso.ISO_SCHED_STREAM_PER_CHUNK)])
-def test_full_size_30b_tp4_2k_cost_balanced_chunks_sampled_rows(n_chunks, sched):
-    wl = iso_inputs.WORKLOADS["30b_tp4_2k"]
+@pytest.mark.parametrize("name,n_chunks,sched", [("30b_tp4_2k", 4, iso.ISO_SCHED_OVERLAP),
+                                                 ("30b_tp4_2k", 4, iso.ISO_SCHED_STREAM_PER_CHUNK),
+                                                 ("30b_tp4_2k", 3, iso.ISO_SCHED_STREAM_PER_CHUNK),
+                                                 ("70b_tp4_8k", 4, iso.ISO_SCHED_STREAM_PER_CHUNK)])
+def test_full_size_cost_balanced_chunks_sampled_rows(name, n_chunks, sched):
+    wl = iso_inputs.WORKLOADS[name]
     dt = wl.dtype
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
     cfg = iso.make_cfg(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, dt, wl.seq)

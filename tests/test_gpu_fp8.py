@@ -122,8 +122,9 @@ def test_small_bf16_layer_with_fp8_projections(hidden, nq, nkv, ffn, T, splits, 
                   "vs exact", orc.max_rel_err(f64(xd), exact["x_out"]))
 
 
-def test_full_size_30b_tp4_2k_fp8_projections_sampled_rows():
-    wl = iso_inputs.WORKLOADS["30b_tp4_2k"]
+@pytest.mark.parametrize("name", ["30b_tp4_2k", "70b_tp8_4k"])
+def test_full_size_fp8_projections_sampled_rows(name):
+    wl = iso_inputs.WORKLOADS[name]
     dt = wl.dtype
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
     rows = iso_inputs.sample_rows(wl.seq, wl.split, 48, seed=0)
@@ -139,7 +140,7 @@ def test_full_size_30b_tp4_2k_fp8_projections_sampled_rows():
             ctx.layer_prefill(w_dev, xd, kc, vc, wl.seq, split, iso.ISO_COMM_D2H)
             ctx.sync()
             err = orc.max_rel_err(f64(xd)[rows], ref["x_out"])
-            print("30b fp8 split", split, "err", err, "rms", rms_rel_err(f64(xd)[rows], ref["x_out"]))
+            print(name, "fp8 split", split, "err", err, "rms", rms_rel_err(f64(xd)[rows], ref["x_out"]))
             assert err <= TOL_LAYER_FP8, (split, err)
             assert rms_rel_err(f64(xd)[rows], ref["x_out"]) <= TOL_RMS_FP8
             assert orc.max_rel_err(f64(kc), ref["k_cache"]) <= TOL_LAYER_FP8

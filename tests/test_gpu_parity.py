@@ -676,8 +676,9 @@ def test_small_bf16_layer_int8_payload():
             _check_sink_codes(ctx, T, hidden, ref["pa"], pm, dt)
 
 
-def test_full_size_30b_tp4_2k_int8_payload_sampled_rows():
-    wl = iso_inputs.WORKLOADS["30b_tp4_2k"]
+@pytest.mark.parametrize("name", ["30b_tp4_2k", "70b_tp8_4k"])
+def test_full_size_int8_payload_sampled_rows(name):
+    wl = iso_inputs.WORKLOADS[name]
     dt = wl.dtype
     x, w = iso_inputs.make_workload_inputs(wl, seed=0)
     rows = iso_inputs.sample_rows(wl.seq, wl.split, 64, seed=0)
@@ -689,6 +690,6 @@ def test_full_size_30b_tp4_2k_int8_payload_sampled_rows():
         out, _, _ = run_layer(ctx, iso.upload_weights(w, dt), x, dt, wl.seq, wl.split, wl.n_kv_heads, wl.head_dim,
                               wl.seq, iso.ISO_COMM_D2H_INT8, poison=True)
         err = orc.max_rel_err(f64(out)[rows], ref["x_out"])
-        print("30b_tp4_2k int8 payload: max_rel_err", err, "bound", TOL_LAYER[dt] + extra)
+        print(name, "int8 payload: max_rel_err", err, "bound", TOL_LAYER[dt] + extra)
         assert err <= TOL_LAYER[dt] + extra
         _check_sink_codes(ctx, wl.seq, wl.hidden, ref["pa"], pm, dt, rows=rows)
