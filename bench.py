@@ -454,26 +454,36 @@ def time_oracle(wl, x_cpu, w_cpu, split, L):
         return {"value": wl.seq / med, "unit": "tokens/s", "cores": cores, "kind": "oracle",
                 "sample": f"full layer, all {wl.seq} tokens, layer_unsplit in float64 numpy: {reps} repetitions, "
                           f"{spent:.1f} s in all, median {med:.2f} s, fastest {times[0]:.2f} s"}
-    # Too large to run whole: the oracle's exact row-sampled form of ONE layer (K/V for every token, everything else
-    # for the sampled output rows) at two sample sizes; its time is linear in the number of rows, t = a + b * rows,
-    # so a full layer is a + b * T and the stack is L such layers.  Extrapolated, and labelled so.
+    # Too large for the full [T, T] definition: the oracle's exact row form of ONE layer (K/V for every token, the rest
+    # per output row).  A probe on T/8 evenly spaced rows and one on T/4 give t = a + b * rows; if a whole layer fits the
+    # budget it is then run on ALL rows and only the factor L (identical layers) is extrapolated, otherwise T/2 rows
+    # are timed and the layer itself is extrapolated too.  Labelled either way.
     T = wl.seq
-    r1, r2 = 64, 320
-    times = []
-    for r in (r1, r2):
-        rows = list(range(0, T, T // r))[:r]
+    def timed(r):
+        rows = list(range(0, T, max(T // r, 1)))[:r]
         t0 = time.perf_counter()
         orc.layer_rows(xn, wn, sh, rows)
-        times.append(time.perf_counter() - t0)
-    b = max((times[1] - times[0]) / (r2 - r1), 1e-9)
-    a = max(times[0] - b * r1, 0.0)
+        return time.perf_counter() - t0
+    r1, r2 = max(T // 8, 64), max(T // 4, 128)
+    t1, t2 = timed(r1), timed(r2)
+    b = max((t2 - t1) / (r2 - r1), 1e-9)
+    a = max(t1 - b * r1, 0.0)
+    unit = "tokens/s" if L == 1 else f"tokens/s through {L} layers"
+    if a + b * T <= 25.0:
+        t_layer = timed(T)
+        return {"value": T / (t_layer * L), "unit": unit, "cores": cores, "kind": "oracle", "extrapolated": L > 1,
+                "sample": f"layer_rows (float64 numpy) of layer 0 on ALL {T} output rows: {t_layer:.1f} s measured (probes on "
+                          f"{r1} / {r2} rows: {t1:.1f} / {t2:.1f} s)" +
+                          (f"; EXTRAPOLATED to {L} identical layers by multiplication" if L > 1 else "")}
+    r3 = max(T // 2, 320)
+    t3 = timed(r3)
+    b = max((t3 - t1) / (r3 - r1), 1e-9)
+    a = max(t1 - b * r1, 0.0)
     t_layer = a + b * T
-    return {"value": T / (t_layer * L), "unit": "tokens/s" if L == 1 else f"tokens/s through {L} layers",
-            "cores": cores, "kind": "oracle", "extrapolated": True,
-            "sample": f"EXTRAPOLATED: layer_rows (float64 numpy) of layer 0 on {r1} and {r2} evenly spaced output rows of "
-                      f"{T}, K/V computed for all tokens: {times[0]:.1f} s and {times[1]:.1f} s -> t = {a:.2f} s + "
+    return {"value": T / (t_layer * L), "unit": unit, "cores": cores, "kind": "oracle", "extrapolated": True,
+            "sample": f"EXTRAPOLATED: layer_rows (float64 numpy) of layer 0 on {r1} and {r3} evenly spaced output rows of "
+                      f"{T}, K/V computed for all tokens: {t1:.1f} s and {t3:.1f} s -> t = {a:.2f} s + "
                       f"{b * 1e3:.2f} ms per output row -> {t_layer:.1f} s for a full layer, times {L} layers"}
-
 
 if __name__ == "__main__":
     sys.exit(main())

@@ -139,9 +139,16 @@ const iso_attn_ws *attn_ws_for(const iso_ctx *ctx, hipStream_t s) {
 hipError_t attn_ws_create(iso_attn_ws *ws) {
     ws->max_slots = ATTN_SLOTS;
     ws->max_blocks = ATTN_BLOCKS;
-    if (hipError_t e = hipMalloc((void **)&ws->part, (size_t)ATTN_SLOTS * iso_attn_part_bytes()); e != hipSuccess) return e;
-    if (hipError_t e = hipMalloc((void **)&ws->cnt, ATTN_BLOCKS * sizeof(unsigned)); e != hipSuccess) return e;
-    return hipMemset(ws->cnt, 0, ATTN_BLOCKS * sizeof(unsigned));
+    hipError_t e = hipMalloc((void **)&ws->part, (size_t)ATTN_SLOTS * iso_attn_part_bytes());
+    if (e == hipSuccess) e = hipMalloc((void **)&ws->cnt, ATTN_BLOCKS * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(ws->cnt, 0, ATTN_BLOCKS * sizeof(unsigned));
+    if (e != hipSuccess) {       // all or nothing: a workspace with one of its two buffers must never reach a launch
+        if (ws->part) (void)hipFree(ws->part);
+        if (ws->cnt) (void)hipFree(ws->cnt);
+        ws->part = nullptr;
+        ws->cnt = nullptr;
+    }
+    return e;
 }
 
 // Row ranges of a GEMM cut into ctx->gemm_segments launches (Section 3.2: several launches per matrix product,
