@@ -26,81 +26,65 @@ template <typename T> __device__ __forceinline__ void store16(T *p, const float 
     *reinterpret_cast<uint4 *>(p) = raw;
 }
 
-// Loads VEC consecutive elements as floats from a buffer of T or of float.
-template <typename T, bool F32> __device__ __forceinline__ void load_vec(const void *base, size_t idx,
-                                                                          float (&out)[16 / sizeof(T)]) {
-    constexpr int VEC = 16 / sizeof(T);
-    if (F32) {
-        const float *p = reinterpret_cast<const float *>(base) + idx;
-#pragma unroll
-        for (int i = 0; i < VEC; i += 4) {
-            const float4 v = *reinterpret_cast<const float4 *>(p + i);
-            out[i] = v.x; out[i + 1] = v.y; out[i + 2] = v.z; out[i + 3] = v.w;
-        }
-    } else {
-        load16<T>(reinterpret_cast<const T *>(base) + idx, out);
-    }
-}
-template <typename T, bool F32> __device__ __forceinline__ void store_vec(void *base, size_t idx,
-                                                                           const float (&in)[16 / sizeof(T)]) {
-    constexpr int VEC = 16 / sizeof(T);
-    if (F32) {
-        float *p = reinterpret_cast<float *>(base) + idx;
-#pragma unroll
-        for (int i = 0; i < VEC; i += 4) *reinterpret_cast<float4 *>(p + i) = make_float4(in[i], in[i + 1], in[i + 2], in[i + 3]);
-    } else {
-        store16<T>(reinterpret_cast<T *>(base) + idx, in);
-    }
-}
-
-// One 256-thread workgroup per token row.  x_new = x (+ delta); optionally written back; optionally
-// y = x_new * rsqrt(mean(x_new^2) + eps) * g.  The first CACHE vectors of each thread stay in
-// registers between the reduction and the scaling, so rows up to 256*CACHE*VEC elements are read once.
-// XIN_F32 / XOUT_F32: the residual stream is read from / written to an fp32 side buffer instead of the
-// T-typed one (the bf16 layer keeps its mid-layer residual unrounded between the two blocks).
+// One 256-thread workgroup per token row.  x_new = x (+ delta (+ delta2)), added in that order in fp32; optionally
+// written to x_out (which may be x itself); optionally y = x_new * rsqrt(mean(x_new^2) + eps) * g.  The first CACHE
+// vectors of each thread stay in registers between the reduction and the scaling, so rows up to 256*CACHE*VEC
+// elements are read once.
+//
+// NDELTA = 2 is how a bf16 layer keeps its mid-layer residual unrounded without storing it: the MLP block's norm
+// computes x1 = x + (attention partial) in registers and writes only y, and the kernel that closes the layer
+// rebuilds the same fp32 x1 from the same two bf16 tensors before it adds the MLP partial (paper Section 2.2: the
+// two partial sums of a layer) -- 16 instead of 20 bytes per element and layer, same bits as an fp32 side buffer.
 //
 // Q8 (bf16 rows of at most 256*CACHE*VEC elements only): instead of y the kernel writes the FP8 (E4M3) codes of
 // y and one fp32 scale per row, exactly as the row quantiser would from the bf16-rounded y: amax = max|y|,
 // code = e4m3(y * (448 / amax)) round to nearest even, scale = amax / 448 (1 for an all-zero row).  The 8-bit
 // projections of the layer (paper Section 4.1) then read their activation operand without a separate pass.
-template <typename T, bool HAS_DELTA, bool WRITE_Y, bool XIN_F32, bool XOUT_F32, bool Q8 = false>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const void *x, const T *__restrict__ delta, void *x_out,
+template <typename T, int NDELTA, bool WRITE_X, bool WRITE_Y, bool Q8 = false>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const T *__restrict__ delta,
+                                                      const T *__restrict__ delta2, T *x_out,
                                                       const T *__restrict__ g, T *__restrict__ y, int H, float eps,
                                                       unsigned char *__restrict__ q8 = nullptr,
                                                       float *__restrict__ q_scale = nullptr) {
+    static_assert(WRITE_X || WRITE_Y, "nothing to write");
+    static_assert(NDELTA > 0 || !WRITE_X, "x is only rewritten when something was added to it");
     constexpr int VEC = 16 / sizeof(T);
     constexpr int CACHE = 4;
     const int tid = threadIdx.x;
     const int nvec = H / VEC;
     const size_t row = (size_t)blockIdx.x * H;
+    // x_new of one 16-byte piece, from the inputs
+    auto load_new = [&](size_t at, float (&v)[VEC]) {
+        load16<T>(x + at, v);
+        if (NDELTA >= 1) {
+            float dv[VEC];
+            load16<T>(delta + at, dv);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) v[i] += dv[i];
+        }
+        if (NDELTA >= 2) {
+            float dv[VEC];
+            load16<T>(delta2 + at, dv);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) v[i] += dv[i];
+        }
+    };
     float vals[CACHE][VEC];
     float ss = 0.f;
 #pragma unroll
     for (int c = 0; c < CACHE; ++c) {
         const int idx = tid + c * 256;
         if (idx < nvec) {
-            load_vec<T, XIN_F32>(x, row + (size_t)idx * VEC, vals[c]);
-            if (HAS_DELTA) {
-                float dv[VEC];
-                load16<T>(delta + row + (size_t)idx * VEC, dv);
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) vals[c][i] += dv[i];
-                store_vec<T, XOUT_F32>(x_out, row + (size_t)idx * VEC, vals[c]);
-            }
+            load_new(row + (size_t)idx * VEC, vals[c]);
+            if (WRITE_X) store16<T>(x_out + row + (size_t)idx * VEC, vals[c]);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) ss += vals[c][i] * vals[c][i];
         }
     }
     for (int idx = tid + CACHE * 256; idx < nvec; idx += 256) {
         float xv[VEC];
-        load_vec<T, XIN_F32>(x, row + (size_t)idx * VEC, xv);
-        if (HAS_DELTA) {
-            float dv[VEC];
-            load16<T>(delta + row + (size_t)idx * VEC, dv);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) xv[i] += dv[i];
-            store_vec<T, XOUT_F32>(x_out, row + (size_t)idx * VEC, xv);
-        }
+        load_new(row + (size_t)idx * VEC, xv);
+        if (WRITE_X) store16<T>(x_out + row + (size_t)idx * VEC, xv);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) ss += xv[i] * xv[i];
     }
@@ -165,10 +149,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *x, const T *__
         }
     }
     for (int idx = tid + CACHE * 256; idx < nvec; idx += 256) {
-        // beyond the register cache: re-read the (already updated) row
+        // beyond the register cache: the row as this thread wrote it (x_out may be x, whose old value is gone),
+        // else rebuilt from the untouched inputs
         float xv[VEC], gv[VEC];
-        if (HAS_DELTA) load_vec<T, XOUT_F32>(x_out, row + (size_t)idx * VEC, xv);
-        else load_vec<T, XIN_F32>(x, row + (size_t)idx * VEC, xv);
+        if (WRITE_X) load16<T>(x_out + row + (size_t)idx * VEC, xv);
+        else load_new(row + (size_t)idx * VEC, xv);
         load16<T>(g + (size_t)idx * VEC, gv);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) gv[i] = xv[i] * scale * gv[i];
@@ -301,55 +286,45 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T *__restrict__ gu, T
     }
 }
 
-template <typename T, bool XIN_F32, bool XOUT_F32>
-hipError_t rmsnorm_dispatch(const void *x, const void *delta, void *x_out, const void *g, void *y, int T_, int H,
-                            float eps, hipStream_t s) {
+template <typename T, bool Q8>
+hipError_t rmsnorm_dispatch(const void *x, const void *delta, const void *delta2, void *x_out, const void *g, void *y,
+                            unsigned char *q8, float *q_scale, int T_, int H, float eps, hipStream_t s) {
     dim3 grid(T_), block(256);
-    const T *dp = (const T *)delta;
-    if (delta && y)
-        hipLaunchKernelGGL((rmsnorm_kernel<T, true, true, XIN_F32, XOUT_F32>), grid, block, 0, s, x, dp, x_out, (const T *)g, (T *)y, H, eps);
-    else if (delta)
-        hipLaunchKernelGGL((rmsnorm_kernel<T, true, false, XIN_F32, XOUT_F32>), grid, block, 0, s, x, dp, x_out, (const T *)g, (T *)y, H, eps);
-    else
-        hipLaunchKernelGGL((rmsnorm_kernel<T, false, true, XIN_F32, XOUT_F32>), grid, block, 0, s, x, dp, x_out, (const T *)g, (T *)y, H, eps);
+    const T *xp = (const T *)x, *d1 = (const T *)delta, *d2 = (const T *)delta2, *gp = (const T *)g;
+    T *xo = (T *)x_out, *yp = (T *)y;
+    const bool wy = Q8 || y != nullptr;
+    if ((delta2 && !delta) || (x_out && !delta) || (!x_out && !wy)) return hipErrorInvalidValue;
+#define ISO_NORM_CASE(ND, WX, WY)                                                                                  \
+    hipLaunchKernelGGL((rmsnorm_kernel<T, ND, WX, WY, Q8 && WY>), grid, block, 0, s, xp, d1, d2, xo, gp, yp, H, eps, q8, \
+                       q_scale)
+    const int nd = delta2 ? 2 : (delta ? 1 : 0);
+    if (nd == 0) ISO_NORM_CASE(0, false, true);
+    else if (nd == 1 && x_out && wy) ISO_NORM_CASE(1, true, true);
+    else if (nd == 1 && x_out) { if (Q8) return hipErrorInvalidValue; ISO_NORM_CASE(1, true, false); }
+    else if (nd == 1) ISO_NORM_CASE(1, false, true);
+    else if (nd == 2 && x_out && wy) ISO_NORM_CASE(2, true, true);
+    else if (nd == 2 && x_out) { if (Q8) return hipErrorInvalidValue; ISO_NORM_CASE(2, true, false); }
+    else ISO_NORM_CASE(2, false, true);
+#undef ISO_NORM_CASE
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta, void *x_out, const void *g, void *y,
-                              int T, int H, float eps, int x_in_f32, int x_out_f32, hipStream_t s) {
-    if (dtype == ISO_F32) return rmsnorm_dispatch<float, false, false>(x, delta, x_out, g, y, T, H, eps, s);
-    if (x_in_f32) return rmsnorm_dispatch<bf16_t, true, false>(x, delta, x_out, g, y, T, H, eps, s);
-    if (x_out_f32) return rmsnorm_dispatch<bf16_t, false, true>(x, delta, x_out, g, y, T, H, eps, s);
-    return rmsnorm_dispatch<bf16_t, false, false>(x, delta, x_out, g, y, T, H, eps, s);
+hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta, const void *delta2, void *x_out,
+                              const void *g, void *y, int T, int H, float eps, hipStream_t s) {
+    if (dtype == ISO_F32) return rmsnorm_dispatch<float, false>(x, delta, delta2, x_out, g, y, nullptr, nullptr, T, H, eps, s);
+    return rmsnorm_dispatch<bf16_t, false>(x, delta, delta2, x_out, g, y, nullptr, nullptr, T, H, eps, s);
 }
 
-// bf16 only: q8[T, H] / q_scale[T] = FP8 row quantisation of rmsnorm(x (+ delta)) * g; with delta, x_out receives
-// x + delta.  x_in_f32 / x_out_f32 as in iso_launch_rmsnorm.  H <= 8192 (the row stays in registers), H % 8 == 0.
+// bf16 only: q8[T, H] / q_scale[T] = FP8 row quantisation of rmsnorm(x (+ delta (+ delta2))) * g; x_out, when given,
+// receives the sum.  H <= 8192 (the row stays in registers), H % 8 == 0.
 bool iso_rmsnorm_fp8_supported(int H) { return H >= 8 && H <= 8192 && (H % 8) == 0; }
 
-hipError_t iso_launch_rmsnorm_fp8(const void *x, const void *delta, void *x_out, const void *g, void *q8, float *q_scale,
-                                  int T, int H, float eps, int x_in_f32, int x_out_f32, hipStream_t s) {
-    if (!iso_rmsnorm_fp8_supported(H) || (x_in_f32 && x_out_f32) || ((x_in_f32 || x_out_f32) && !delta))
-        return hipErrorInvalidValue;
-    dim3 grid(T), block(256);
-    const bf16_t *dp = (const bf16_t *)delta, *gp = (const bf16_t *)g;
-    bf16_t *no_y = nullptr;
-    unsigned char *qp = (unsigned char *)q8;
-    if (!delta)
-        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, false, true, false, false, true>), grid, block, 0, s, x, dp, x_out, gp,
-                           no_y, H, eps, qp, q_scale);
-    else if (x_in_f32)
-        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, true, true, true, false, true>), grid, block, 0, s, x, dp, x_out, gp,
-                           no_y, H, eps, qp, q_scale);
-    else if (x_out_f32)
-        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, true, true, false, true, true>), grid, block, 0, s, x, dp, x_out, gp,
-                           no_y, H, eps, qp, q_scale);
-    else
-        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, true, true, false, false, true>), grid, block, 0, s, x, dp, x_out, gp,
-                           no_y, H, eps, qp, q_scale);
-    return hipGetLastError();
+hipError_t iso_launch_rmsnorm_fp8(const void *x, const void *delta, const void *delta2, void *x_out, const void *g,
+                                  void *q8, float *q_scale, int T, int H, float eps, hipStream_t s) {
+    if (!iso_rmsnorm_fp8_supported(H)) return hipErrorInvalidValue;
+    return rmsnorm_dispatch<bf16_t, true>(x, delta, delta2, x_out, g, nullptr, (unsigned char *)q8, q_scale, T, H, eps, s);
 }
 
 hipError_t iso_launch_rope_kv(int dtype, void *qkv, void *k_cache, void *v_cache, const float *cos_t,

@@ -41,7 +41,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 int n_qkv(const iso_cfg &c) { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
 
 struct WsLayout {
-    size_t y, qkv, attn, part, gu, act, x1f, q8, a8, a8s, a8_pitch, total;
+    size_t y, qkv, attn, part, part_m, gu, act, q8, a8, a8s, a8_pitch, total;
 };
 
 WsLayout ws_layout(const iso_cfg &c) {
@@ -53,9 +53,9 @@ WsLayout ws_layout(const iso_cfg &c) {
     l.qkv = take(t * n_qkv(c));
     l.attn = take(t * c.n_q_heads * c.head_dim);
     l.part = take(t * c.hidden);
+    l.part_m = take(t * c.hidden);
     l.gu = take(t * 2 * c.ffn);
     l.act = take(t * c.ffn);
-    l.x1f = take(c.dtype == ISO_BF16 ? t * c.hidden * 2 : 0);   // fp32 = two bf16 slots per element
     l.q8 = take((t * (c.hidden + 16) + e - 1) / e);
     size_t kmax = (size_t)c.hidden;
     if ((size_t)c.n_q_heads * c.head_dim > kmax) kmax = (size_t)c.n_q_heads * c.head_dim;
@@ -259,7 +259,7 @@ int sk_status(const iso_ctx *ctx) {
 int comm_point(iso_ctx *ctx, int comm, int which, int lo, int n, hipStream_t s) {
     const iso_cfg &c = ctx->cfg;
     const size_t e = ctx->elt, H = (size_t)c.hidden;
-    char *partr = (char *)ctx->part + (size_t)lo * H * e;
+    char *partr = (char *)(which ? ctx->part_m : ctx->part) + (size_t)lo * H * e;
     char *sink = (char *)ctx->host_sink + (size_t)which * c.max_seq * H * e;
     if (comm == ISO_COMM_D2H) {
         Timed t_(ctx, ISO_K_COMM, s);
@@ -289,25 +289,24 @@ int attn_block_head(iso_ctx *ctx, const iso_weights *w, void *x, void *kc, void 
     char *xr = at(x, ck.lo, H, e);
     char *yr = at(ctx->y, ck.lo, H, e);
     char *qkvr = at(ctx->qkv, ck.lo, NQKV, e);
-    const bool hi = c.dtype == ISO_BF16;     // mid-layer residual lives in the fp32 side buffer
     // 8-bit projection: the norm writes the FP8 codes and row scales of y itself, y is never stored
     F8Arg f8{w->w_qkv_f8, w->s_qkv, ck.lo};
     f8.prequant = use_fp8(ctx, f8, ck.n, NQKV, H) && iso_rmsnorm_fp8_supported(H);
     unsigned char *a8 = ctx->a8 + (size_t)ck.lo * ctx->a8_pitch;
     float *sa = ctx->a8s + ck.lo;
-    if (add_prev_partial) {   // x = x1 + (previous layer's MLP partial), y = norm(x)
-        void *xin = hi ? (void *)(ctx->x1f + (size_t)ck.lo * H) : (void *)xr;
+    if (add_prev_partial) {   // x = (x + previous layer's attention partial) + its MLP partial, y = norm(x)
+        const char *pa = at(ctx->part, ck.lo, H, e), *pm = at(ctx->part_m, ck.lo, H, e);
         if (f8.prequant)
-            LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm_fp8(xin, at(ctx->part, ck.lo, H, e), xr, w->g_attn, a8, sa, ck.n, H,
-                       c.rms_eps, hi, 0, ck.s), "residual+rmsnorm+fp8");
+            LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm_fp8(xr, pa, pm, xr, w->g_attn, a8, sa, ck.n, H, c.rms_eps, ck.s),
+                       "residual+rmsnorm+fp8");
         else
-            LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xin, at(ctx->part, ck.lo, H, e), xr, w->g_attn, yr, ck.n, H,
-                       c.rms_eps, hi, 0, ck.s), "residual+rmsnorm");
+            LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, pa, pm, xr, w->g_attn, yr, ck.n, H, c.rms_eps, ck.s),
+                       "residual+rmsnorm");
     } else if (f8.prequant) {
-        LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm_fp8(xr, nullptr, nullptr, w->g_attn, a8, sa, ck.n, H, c.rms_eps, 0, 0, ck.s),
+        LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm_fp8(xr, nullptr, nullptr, nullptr, w->g_attn, a8, sa, ck.n, H, c.rms_eps, ck.s),
                    "rmsnorm+fp8");
     } else {
-        LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, nullptr, nullptr, w->g_attn, yr, ck.n, H, c.rms_eps, 0, 0, ck.s), "rmsnorm");
+        LAUNCH_TRY(ISO_K_RMSNORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, nullptr, nullptr, nullptr, w->g_attn, yr, ck.n, H, c.rms_eps, ck.s), "rmsnorm");
     }
     // bf16 layers with head_dim 128: rotary embedding and KV-cache write ride in the projection's epilogue whenever
     // the launch rule picks a kernel whose waves own whole heads (the 256-wide tile or its stream-K launch)
@@ -361,22 +360,22 @@ int mlp_block(iso_ctx *ctx, const iso_weights *w, void *x, const Chunk &ck, int 
     const int H = c.hidden, F = c.ffn;
     char *xr = at(x, ck.lo, H, e);
     char *yr = at(ctx->y, ck.lo, H, e);
-    char *partr = at(ctx->part, ck.lo, H, e);
+    const char *pa = at(ctx->part, ck.lo, H, e);
+    char *partr = at(ctx->part_m, ck.lo, H, e);
     char *gur = at(ctx->gu, ck.lo, 2 * (size_t)F, e);
     char *actr = at(ctx->act, ck.lo, F, e);
-    const bool hi = c.dtype == ISO_BF16;
-    // x1 = x + (attention partial); y = norm(x1).  bf16 layers keep x1 unrounded in the fp32 side buffer.
+    // y = norm(x1), x1 = x + (attention partial) held in registers only: the kernel that closes the layer rebuilds
+    // it from the same two tensors, so the mid-layer residual is never rounded and never stored.
     // With an 8-bit gate/up projection the norm leaves the FP8 codes and row scales of y instead of y.
     F8Arg f8gu{w->w_gate_up_f8, w->s_gate_up, ck.lo};
     f8gu.prequant = use_fp8(ctx, f8gu, ck.n, 2 * F, H) && iso_rmsnorm_fp8_supported(H);
     unsigned char *a8 = ctx->a8 + (size_t)ck.lo * ctx->a8_pitch;
     float *sa = ctx->a8s + ck.lo;
-    void *x1 = hi ? (void *)(ctx->x1f + (size_t)ck.lo * H) : (void *)xr;
     if (f8gu.prequant)
-        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm_fp8(xr, partr, x1, w->g_mlp, a8, sa, ck.n, H, c.rms_eps, 0, hi, ck.s),
+        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm_fp8(xr, pa, nullptr, nullptr, w->g_mlp, a8, sa, ck.n, H, c.rms_eps, ck.s),
                    "residual+rmsnorm+fp8");
     else
-        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, partr, x1, w->g_mlp, yr, ck.n, H, c.rms_eps, 0, hi, ck.s),
+        LAUNCH_TRY(ISO_K_RESID_NORM, ck.s, iso_launch_rmsnorm(c.dtype, xr, pa, nullptr, nullptr, w->g_mlp, yr, ck.n, H, c.rms_eps, ck.s),
                    "residual+rmsnorm");
     const bool fused = c.dtype == ISO_BF16 && !(ctx->flags & (ISO_FLAG_SIMPLE_GEMM | ISO_FLAG_GEMM_STAGED | ISO_FLAG_NO_FUSE)) &&
                        iso_gemm_swiglu_bf16_supported(ck.n, F, H);
@@ -410,9 +409,8 @@ int final_residual(iso_ctx *ctx, void *x, const Chunk &ck) {
     const iso_cfg &c = ctx->cfg;
     const size_t e = ctx->elt;
     char *xr = at(x, ck.lo, c.hidden, e);
-    const bool hi = c.dtype == ISO_BF16;
-    LAUNCH_TRY(ISO_K_RESIDUAL, ck.s, iso_launch_rmsnorm(c.dtype, hi ? (void *)(ctx->x1f + (size_t)ck.lo * c.hidden) : (void *)xr,
-               at(ctx->part, ck.lo, c.hidden, e), xr, nullptr, nullptr, ck.n, c.hidden, c.rms_eps, hi, 0, ck.s), "residual");
+    LAUNCH_TRY(ISO_K_RESIDUAL, ck.s, iso_launch_rmsnorm(c.dtype, xr, at(ctx->part, ck.lo, c.hidden, e), at(ctx->part_m, ck.lo, c.hidden, e),
+               xr, nullptr, nullptr, ck.n, c.hidden, c.rms_eps, ck.s), "residual");
     return ISO_OK;
 }
 
@@ -636,8 +634,7 @@ int iso_create(iso_ctx **out, const iso_cfg *cfg, void *stream0, void *stream1) 
         ctx->ws_bytes = l.total;
         char *b = (char *)ctx->ws;
         ctx->y = b + l.y; ctx->qkv = b + l.qkv; ctx->attn = b + l.attn;
-        ctx->part = b + l.part; ctx->gu = b + l.gu; ctx->act = b + l.act;
-        ctx->x1f = (float *)(b + l.x1f);
+        ctx->part = b + l.part; ctx->part_m = b + l.part_m; ctx->gu = b + l.gu; ctx->act = b + l.act;
         ctx->q8 = (signed char *)(b + l.q8);
         ctx->a8 = (unsigned char *)(b + l.a8);
         ctx->a8s = (float *)(b + l.a8s);
@@ -784,7 +781,7 @@ int iso_rmsnorm_fp8(iso_ctx *ctx, void *x, const void *delta, const void *g, voi
     if (!iso_rmsnorm_fp8_supported(ctx->cfg.hidden))
         return fail(ISO_ERR_SHAPE, "hidden=%d: the fused norm + FP8 quantiser takes rows of at most 8192 elements", ctx->cfg.hidden);
     LAUNCH_TRY(delta ? ISO_K_RESID_NORM : ISO_K_RMSNORM, (hipStream_t)stream,
-               iso_launch_rmsnorm_fp8(x, delta, delta ? x : nullptr, g, q, scale, T, ctx->cfg.hidden, ctx->cfg.rms_eps, 0, 0,
+               iso_launch_rmsnorm_fp8(x, delta, nullptr, delta ? x : nullptr, g, q, scale, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
                                       (hipStream_t)stream), "rmsnorm+fp8");
     return ISO_OK;
 }
@@ -985,8 +982,8 @@ int iso_rmsnorm(iso_ctx *ctx, const void *x, const void *g, void *y, int T, void
     if (!ctx) return fail(ISO_ERR_NULL, "ctx is NULL");
     if (!x || !g || !y) return fail(ISO_ERR_NULL, "x, g and y must be non-NULL");
     if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
-    LAUNCH_TRY(ISO_K_RMSNORM, (hipStream_t)stream, iso_launch_rmsnorm(ctx->cfg.dtype, x, nullptr, nullptr, g, y, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
-                                  0, 0, (hipStream_t)stream), "rmsnorm");
+    LAUNCH_TRY(ISO_K_RMSNORM, (hipStream_t)stream, iso_launch_rmsnorm(ctx->cfg.dtype, x, nullptr, nullptr, nullptr, g, y, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
+                                  (hipStream_t)stream), "rmsnorm");
     return ISO_OK;
 }
 
@@ -995,8 +992,8 @@ int iso_residual_rmsnorm(iso_ctx *ctx, void *x, const void *delta, const void *g
     if (!x || !delta) return fail(ISO_ERR_NULL, "x and delta must be non-NULL");
     if ((y != nullptr) != (g != nullptr)) return fail(ISO_ERR_NULL, "g and y must both be given or both be NULL");
     if (T < 1) return fail(ISO_ERR_SHAPE, "T=%d must be positive", T);
-    LAUNCH_TRY(y ? ISO_K_RESID_NORM : ISO_K_RESIDUAL, (hipStream_t)stream, iso_launch_rmsnorm(ctx->cfg.dtype, x, delta, x, g, y, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
-                                  0, 0, (hipStream_t)stream), "residual+rmsnorm");
+    LAUNCH_TRY(y ? ISO_K_RESID_NORM : ISO_K_RESIDUAL, (hipStream_t)stream, iso_launch_rmsnorm(ctx->cfg.dtype, x, delta, nullptr, x, g, y, T, ctx->cfg.hidden, ctx->cfg.rms_eps,
+                                  (hipStream_t)stream), "residual+rmsnorm");
     return ISO_OK;
 }
 

@@ -49,11 +49,11 @@ struct iso_ctx {
     void *y;           // [max_seq, hidden]   normed activations (both norms)
     void *qkv;         // [max_seq, n_qkv]
     void *attn;        // [max_seq, nq*d]
-    void *part;        // [max_seq, hidden]   row-parallel partial (o_proj, then down)
+    void *part;        // [max_seq, hidden]   row-parallel partial of the attention block (o_proj)
+    void *part_m;      // [max_seq, hidden]   row-parallel partial of the MLP block (down); both live until the layer closes
     void *gu;          // [max_seq, 2*ffn]
     void *act;         // [max_seq, ffn]
     signed char *q8;   // [max_seq, hidden + 16] int8 codes + fp32 scale per row (ISO_COMM_D2H_INT8)
-    float *x1f;        // [max_seq, hidden] fp32: residual stream between the two blocks of a bf16 layer
     unsigned char *a8; // [max_seq, max(hidden, nq*d, ffn)] FP8 copy of the current projection input (bf16 contexts)
     float *a8s;        // [max_seq] its row scales
     size_t a8_pitch;   // bytes per token of a8
@@ -73,9 +73,9 @@ struct iso_ctx {
 constexpr int ISO_MAX_TIMED = 65536;
 
 // ---- launchers; each validates nothing (callers do) and returns the launch status -------------
-hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta_or_null, void *x_out_or_null,
-                              const void *g, void *y_or_null, int T, int H, float eps, int x_in_f32, int x_out_f32,
-                              hipStream_t s);   // x_in_f32 / x_out_f32: bf16 layers only, residual in an fp32 side buffer
+// x_new = x (+ delta (+ delta2)); x_out (may be x) receives it when given; y = rmsnorm(x_new) * g when given
+hipError_t iso_launch_rmsnorm(int dtype, const void *x, const void *delta_or_null, const void *delta2_or_null,
+                              void *x_out_or_null, const void *g, void *y_or_null, int T, int H, float eps, hipStream_t s);
 hipError_t iso_launch_rope_kv(int dtype, void *qkv, void *k_cache, void *v_cache, const float *cos_t,
                               const float *sin_t, int Tc, int q_offset, int nq, int nkv, int d, hipStream_t s);
 hipError_t iso_launch_quant_rows(int dtype, void *part, void *q8, int T, int H, hipStream_t s);
@@ -101,8 +101,8 @@ int iso_gemm_sk_max_wg(void);
 bool iso_gemm_swiglu_bf16_supported(int M, int F, int K);
 bool iso_gemm_fp8_supported(int M, int N, int K);
 bool iso_rmsnorm_fp8_supported(int H);
-hipError_t iso_launch_rmsnorm_fp8(const void *x, const void *delta_or_null, void *x_out_or_null, const void *g, void *q8,
-                                  float *q_scale, int T, int H, float eps, int x_in_f32, int x_out_f32, hipStream_t s);
+hipError_t iso_launch_rmsnorm_fp8(const void *x, const void *delta_or_null, const void *delta2_or_null, void *x_out_or_null,
+                                  const void *g, void *q8, float *q_scale, int T, int H, float eps, hipStream_t s);
 hipError_t iso_launch_quant_rows_fp8(const void *x, void *q, float *scale, int rows, int cols, hipStream_t s);
 hipError_t iso_launch_gemm_fp8(const void *a8, const float *sa, const void *w8, const float *sw, void *c, int M, int N,
                                int K, int variant, iso_sk_ws *sk_or_null, hipStream_t s);

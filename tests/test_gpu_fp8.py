@@ -256,8 +256,8 @@ def test_norm_with_fp8_tail_rejects_wide_rows_and_fp32():
 
 
 def test_two_layer_stack_with_fp8_projections():
-    """Layer 2's first norm takes the residual from the fp32 side buffer: that variant of the fused norm + quantiser
-    only runs inside a stack."""
+    """Layer 2's first norm closes layer 1 (x + attention partial + MLP partial): that variant of the fused norm +
+    quantiser only runs inside a stack."""
     hidden, nq, nkv, d, ffn, T, dt = 512, 4, 1, 128, 768, 300, "bf16"
     layers = [iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=40 + l, dtype=dt) for l in range(2)]
     x = iso_inputs.make_hidden(T, hidden, seed=6, dtype=dt)
