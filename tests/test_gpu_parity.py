@@ -484,6 +484,30 @@ def test_two_layer_stack_equals_two_oracle_layers():
             assert orc.max_rel_err(f64(xd), ref) <= 2 * TOL_LAYER["bf16"]
 
 
+@pytest.mark.parametrize("dt,hidden", [("bf16", 8256), ("f32", 4224)])
+def test_two_layer_stack_with_rows_longer_than_the_norm_kernels_register_cache(dt, hidden):
+    """Rows beyond 256 threads x 4 cached 16-byte pieces (8192 bf16 / 4096 fp32 elements) take the norm kernels'
+    second loops: the mid-layer norm rebuilds x + attention partial there from its inputs, the kernel that closes a
+    layer re-reads the row it has just written in place."""
+    nq, nkv, d, ffn, T, split = 2, 1, 128, 256, 70, 33
+    layers = [iso_inputs.make_layer(hidden, nq, nkv, d, ffn, seed=60 + l, dtype=dt) for l in range(2)]
+    x = iso_inputs.make_hidden(T, hidden, seed=6, dtype=dt)
+    sh = shape_of(hidden, nq, nkv, d, ffn)
+    ref = h64(x, dt)
+    for w in layers:
+        ref = orc.layer_unsplit(ref, oracle_weights(w, dt), sh)["x_out"]
+    layers_dev = [iso.upload_weights(w, dt) for w in layers]
+    with make_ctx(hidden, nq, nkv, d, ffn, dt, T) as ctx:
+        for s in (0, split):
+            xd = dev(x, dt)
+            kcs = iso.DeviceArray((2, T, nkv, d), dt, fill_byte=NAN_BYTE)
+            vcs = iso.DeviceArray((2, T, nkv, d), dt, fill_byte=NAN_BYTE)
+            ctx.stack_prefill(layers_dev, xd, kcs, vcs, T, s, iso.ISO_COMM_D2H)
+            ctx.sync()
+            err = orc.max_rel_err(f64(xd), ref)
+            assert err <= 2 * TOL_LAYER[dt], (s, err)
+
+
 def test_kv_event_orders_the_chunks_and_runs_are_bit_identical():
     """Chunk 1 must not read the cache before chunk 0 wrote it (Section 3.1).  The cache starts as NaN, so a
     read that overtook the write would surface as NaN; repeated runs must also agree bit for bit."""
