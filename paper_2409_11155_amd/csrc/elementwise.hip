@@ -18,6 +18,17 @@ template <typename T> __device__ __forceinline__ void load16(const T *p, float (
     for (int i = 0; i < (int)(16 / sizeof(T)); ++i) out[i] = iso_to_f32(e[i]);
 }
 
+// The same for data that is read once (token rows): a non-temporal load leaves the L2 to the tiles of the GEMM that
+// runs beside this kernel on the other chunk's stream (the residual kernels measure 6-7 % faster with it; the same
+// hint on their stores costs 5 %).
+template <typename T> __device__ __forceinline__ void load16_stream(const T *p, float (&out)[16 / sizeof(T)]) {
+    typedef unsigned u32x4_nt __attribute__((ext_vector_type(4)));
+    u32x4_nt raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt *>(p));
+    const T *e = reinterpret_cast<const T *>(&raw);
+#pragma unroll
+    for (int i = 0; i < (int)(16 / sizeof(T)); ++i) out[i] = iso_to_f32(e[i]);
+}
+
 template <typename T> __device__ __forceinline__ void store16(T *p, const float (&in)[16 / sizeof(T)]) {
     uint4 raw;
     T *e = reinterpret_cast<T *>(&raw);
@@ -55,16 +66,16 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const T *__res
     const size_t row = (size_t)blockIdx.x * H;
     // x_new of one 16-byte piece, from the inputs
     auto load_new = [&](size_t at, float (&v)[VEC]) {
-        load16<T>(x + at, v);
+        load16_stream<T>(x + at, v);
         if (NDELTA >= 1) {
             float dv[VEC];
-            load16<T>(delta + at, dv);
+            load16_stream<T>(delta + at, dv);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) v[i] += dv[i];
         }
         if (NDELTA >= 2) {
             float dv[VEC];
-            load16<T>(delta2 + at, dv);
+            load16_stream<T>(delta2 + at, dv);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) v[i] += dv[i];
         }
