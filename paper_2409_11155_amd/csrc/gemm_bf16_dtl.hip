@@ -48,7 +48,7 @@ hipError_t launch_sk(const void *a, const void *w, void *c, int M, int N, int K,
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     int TS, G, grouped;
     sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped);
-    ++sk->epoch;
+    if (++sk->epoch == 0) sk->epoch = 1;   // 0 is what a never-raised flag holds
     dim3 grid(G), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)c, M, N,
                        K, tiles_m, tiles_n, (unsigned char *)sk->base, sk->epoch, sk->err, TS, grouped, RopeArgs{});
@@ -257,7 +257,7 @@ hipError_t iso_launch_gemm_qkv_rope_bf16(const void *a, const void *w, void *qkv
         return e;
     int TS, G, grouped;
     sk_plan(M, N, K, sk->num_wg, &TS, &G, &grouped);
-    ++sk->epoch;
+    if (++sk->epoch == 0) sk->epoch = 1;   // 0 is what a never-raised flag holds
     hipLaunchKernelGGL(kern, dim3(G), dim3(Cfg::NT), LDS_BYTES, s, (const bf16_t *)a, (const bf16_t *)w, (bf16_t *)qkv, M, N,
                        K, tiles_m, tiles_n, (unsigned char *)sk->base, sk->epoch, sk->err, TS, grouped, rope);
     return hipGetLastError();

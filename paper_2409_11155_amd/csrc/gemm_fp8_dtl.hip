@@ -41,7 +41,7 @@ hipError_t launch_sk(const void *a, const void *w, const float *sa, const float 
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     int TS, G, grouped;
     iso_gemm_sk_plan(M, N, K / KE, sk->num_wg, &TS, &G, &grouped);
-    ++sk->epoch;
+    if (++sk->epoch == 0) sk->epoch = 1;   // 0 is what a never-raised flag holds
     dim3 grid(G), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, s, (const unsigned char *)a, (const unsigned char *)w, sa, sw,
                        (bf16_t *)c, M, N, K, tiles_m, tiles_n, (unsigned char *)sk->base, sk->epoch, sk->err, TS, grouped);
